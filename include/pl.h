@@ -1,0 +1,230 @@
+/*
+ * pl.h - C ABI of the constant-batch decode engine with in-flight weight updates (gfx950).
+ *
+ * The engine is the generation side of the Actor loop of the PipelineRL paper (Alg. 2): keep H
+ * sequences in flight, produce one token per sequence per step, refill a slot as soon as its
+ * sequence finishes, and take a new set of weights between two steps without discarding any
+ * sequence's key/value history (Sec. 4; Sec. 5.1 for the stale-cache semantics).  Every emitted
+ * token carries the log-probability it had under the weights that sampled it (the behaviour
+ * policy mu of the truncated importance-sampling estimator, Sec. 2.1) and the version number of
+ * those weights (token lag, Fig. 3).
+ *
+ * Conventions
+ *   - Every function returns a pl_status (0 = success, negative = error) unless stated otherwise;
+ *     nothing throws or aborts across this boundary.  pl_last_error() returns a NUL-terminated
+ *     message owned by the library, valid until the next call on the same thread.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP device memory on
+ *     the engine's GPU.  The caller owns every buffer it passes; the engine copies what it keeps.
+ *   - An engine is bound to one GPU and must be driven from one host thread at a time.
+ *   - All floating-point storage on the device is bf16 unless stated; accumulation is fp32.
+ */
+#ifndef PL_H
+#define PL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PL_OK = 0,
+  PL_E_INVAL = -1,  /* bad configuration, shape, size, pointer or temperature <= 0          */
+  PL_E_NOSLOT = -2, /* all max_batch slots are occupied                                      */
+  PL_E_NOKV = -3,   /* KV page pool exhausted; the engine state is unchanged                 */
+  PL_E_BUSY = -4,   /* a weight update is still being staged                                 */
+  PL_E_STATE = -5,  /* call not valid in this state (idle slot, no weights loaded, ...)      */
+  PL_E_CTX = -6,    /* sequence would grow past max_context                                  */
+  PL_E_HIP = -7,    /* a HIP call failed; the engine should be destroyed                     */
+  PL_E_NOMEM = -8   /* host or device allocation failed                                      */
+} pl_status;
+
+#define PL_SWAP_ASYNC 0u /* stage in the background; flip at the first step boundary once staged */
+#define PL_SWAP_WAIT 1u  /* the next step waits for the staging copy, then flips                  */
+#define PL_DEVICE_NONE (-1) /* bookkeeping-only engine: no GPU is touched, no token is computed  */
+
+typedef struct pl_engine pl_engine;
+
+/* Decoder shape and engine capacity.  The network is a pre-norm decoder with RMSNorm, rotary
+ * positions (half-split pairing: element i rotates with element i + head_dim/2, angle
+ * pos * rope_theta^(-2i/head_dim)), grouped-query attention (query head h reads kv head
+ * h / (n_q_heads / n_kv_heads)), SwiGLU feed-forward, untied LM head, no biases. */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_theta; /* e.g. 1e4 */
+  float rms_eps;    /* added to the mean square inside the root, e.g. 1e-6 */
+  int32_t max_batch;      /* H of Alg. 2: number of slots */
+  int32_t max_context;    /* cap on prompt + generated positions of one sequence */
+  int64_t kv_pool_tokens; /* capacity of the paged KV pool, in token positions (all layers) */
+  int32_t kv_page_tokens; /* tokens per page: multiple of 32; 0 selects 64 */
+  int32_t n_weight_buffers; /* 2: in-flight updates are staged into the inactive buffer; 1: updates
+                               overwrite the only buffer and always block */
+  uint64_t seed;          /* sampler key */
+  int32_t device;         /* HIP device ordinal, or PL_DEVICE_NONE */
+} pl_model_cfg;
+
+/* Result of one decode step: one entry per occupied slot, in slot order.  Arrays are caller
+ * allocated with room for max_batch entries; any of the array pointers may be NULL. */
+typedef struct {
+  int32_t n;                /* out: number of entries */
+  int32_t *slot;            /* out: slot index */
+  uint64_t *seq_id;         /* out: caller's sequence id */
+  int32_t *token;           /* out: token produced by this step (sampled or forced) */
+  float *logprob;           /* out: log softmax(logits / T)[token] under the step's weights */
+  uint32_t *weight_version; /* out: version of the weights that produced the token */
+  int32_t *position;        /* out: position of the token that was consumed (0-based) */
+  uint8_t *emitted;         /* out: 1 if `token` is a generated token, 0 while the prompt is read */
+  uint8_t *finished;        /* out: 1 if this was the sequence's last token (max_new reached) */
+  float step_ms;            /* out: GPU time of the step on the decode stream */
+  float swap_stall_ms;      /* out: time this step spent waiting for a staged weight copy */
+} pl_step_out;
+
+typedef struct {
+  uint64_t steps;             /* decode steps run */
+  uint64_t tokens_emitted;    /* generated tokens */
+  uint64_t slot_steps;        /* sum over steps of occupied slots (prompt reading included) */
+  uint64_t swaps;             /* weight updates that became active */
+  double gpu_ms_total;        /* sum of step_ms */
+  double algorithmic_bytes;   /* sum over steps of streamed weight bytes + KV bytes read + written */
+  float last_swap_copy_ms;    /* duration of the last staging copy */
+  uint32_t active_version;
+  int64_t kv_pages_free, kv_pages_total;
+} pl_stats;
+
+/* ---- engine life cycle --------------------------------------------------------------------- */
+
+/* Create an engine: allocates weight buffer(s), the KV page pool and work buffers on cfg->device.
+ * PL_E_INVAL if a shape is unsupported (head_dim not in {32, 64, 128}, n_q_heads not a multiple
+ * of n_kv_heads or group > 16, d_model or d_ffn not a multiple of 64, ...). */
+int pl_create(const pl_model_cfg *cfg, pl_engine **out);
+void pl_destroy(pl_engine *e);
+const char *pl_last_error(void);
+
+/* ---- weights --------------------------------------------------------------------------------
+ * Weights travel as one flat bf16 blob.  pl_weight_layout enumerates its tensors: for idx in
+ * [0, pl_weight_count) it returns the tensor's name, element offset into the blob and shape
+ * [rows, cols] (cols = 1 for gains).  Tensors, in order: "embed" [vocab, d]; per layer l:
+ * "l<l>.g1" [d], "l<l>.w_qkv" [(Hq + 2 Hkv) hd, d] (rows: all q heads, all k heads, all v heads),
+ * "l<l>.w_o" [d, Hq hd], "l<l>.g2" [d], "l<l>.w_gu" [2 F, d] (gate and up rows interleaved in
+ * blocks of 32: rows [64 t, 64 t + 32) are gate rows 32 t .., rows [64 t + 32, 64 t + 64) the
+ * matching up rows), "l<l>.w_d" [d, F]; then "gf" [d] and "lm_head" [vocab, d].  Every matrix is
+ * row-major [out_features, in_features]: y = x W^T. */
+int32_t pl_weight_count(const pl_engine *e);
+int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t *offset_elems,
+                     int64_t shape[2]);
+int64_t pl_weight_nbytes(const pl_engine *e);
+
+/* Blocking load of version 0 (or a blocking replacement of the active buffer, version + 1, if
+ * weights are already loaded).  src: host or device pointer to pl_weight_nbytes bytes. */
+int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes);
+
+/* In-flight weight update ("mu <- receive_weight_update()", Alg. 2).  Starts copying the blob at
+ * src (host - pinned for a truly asynchronous copy - or device memory) into the inactive buffer
+ * on a side stream and returns at once.  The engine flips to the new buffer only between two
+ * decode steps: with PL_SWAP_WAIT at the very next step (which first waits for the copy), with
+ * PL_SWAP_ASYNC at the first step that finds the copy complete.  No KV page is touched: tokens
+ * produced after the flip are conditioned on keys/values computed under older weights (Sec. 5.1).
+ * src must stay valid and unmodified until the flip.  *out_new_version receives the version the
+ * new weights will carry.  PL_E_BUSY if an update is already staged and not yet active;
+ * PL_E_STATE before pl_load_weights.  With n_weight_buffers == 1 the copy overwrites the active
+ * buffer on the decode stream and the call returns when it is done. */
+int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flags,
+                    uint32_t *out_new_version);
+int pl_swap_poll(pl_engine *e, int32_t *staged_ready, uint32_t *active_version);
+
+/* ---- sequences (Alg. 2: pop finished, refill to H) ------------------------------------------- */
+
+/* Admit a sequence into the lowest free slot.  The engine copies the prompt.  The sequence reads
+ * its prompt one token per step (positions 0 .. n_prompt-1); the step that reads the last prompt
+ * token emits the first generated token; it is finished after max_new emitted tokens.
+ * PL_E_CTX if n_prompt + max_new - 1 > max_context; PL_E_NOKV if the pool cannot hold the
+ * prompt; PL_E_NOSLOT if the batch is full; PL_E_INVAL for temperature <= 0, empty prompt,
+ * token out of range. */
+int pl_add_sequence(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
+                    int32_t max_new, float temperature, int32_t *out_slot);
+/* Free a slot and its KV pages (finished or not).  PL_E_STATE if the slot is idle. */
+int pl_retire_sequence(pl_engine *e, int32_t slot);
+int32_t pl_num_active(const pl_engine *e);
+
+/* ---- the step ("generate next tokens with mu", Alg. 2) ---------------------------------------
+ * One token for every occupied slot.  forced (host, may be NULL): forced[slot] >= 0 replaces the
+ * token this step would sample for that slot (teacher forcing; its log-prob is still recorded and
+ * it is what the next step consumes); -1 samples.  Blocks until the step's outputs are in `out`.
+ * Sampling is Gumbel-max over logits / T with Philox4x32-10 noise keyed by (seed; seq_id,
+ * position, vocabulary index), so a sequence's draws do not depend on its slot or neighbours.
+ * PL_E_NOKV if a sequence needs a new page and none is free (nothing is executed). */
+int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out);
+
+int pl_get_stats(pl_engine *e, pl_stats *out);
+
+/* ---- test and benchmark hooks -----------------------------------------------------------------*/
+
+/* fp32 logits [n, vocab] of the last step (host out), rows in the order of that step's entries. */
+int pl_debug_get_logits(pl_engine *e, float *out, int64_t out_elems);
+/* Keys (after rotation) and values of one slot and layer as host fp32 [n_ctx, n_kv_heads, hd]. */
+int pl_debug_read_kv(pl_engine *e, int32_t slot, int32_t layer, float *k_out, float *v_out,
+                     int32_t n_ctx);
+int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_in,
+                      const float *v_in, int32_t n_ctx);
+/* Admit a sequence as if it had already run for `context_len` positions (>= n_prompt - 1 ... the
+ * prompt is not needed then and may be NULL when context_len >= n_prompt): pages for
+ * context_len positions are allocated, their contents left as they are in the pool; n_emitted
+ * tokens count as generated; last_token is what the next step consumes. */
+int pl_debug_add_sequence_at(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
+                             int32_t max_new, float temperature, int32_t context_len,
+                             int32_t n_emitted, int32_t last_token, int32_t *out_slot);
+/* Device pointer and size of the KV page pool (to fill it with synthetic values). */
+int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
+
+/* ---- kernel-level entry points (device pointers; `stream` is a hipStream_t or NULL) ----------- */
+
+/* Ragged grouped-query decode attention over a paged bf16 cache: for every sequence b < n_seq and
+ * query head h, out[b, h, :] = sum_j softmax_j(q[b, h] . K_b[j, h / group] / sqrt(hd)) V_b[j, h / group],
+ * j < ctx_len[b].
+ *   q          device bf16 [n_seq, n_q_heads, hd]
+ *   kv_pages   device bf16 page pool of one layer; page p, kv head g starts at element
+ *              (p * n_kv_heads + g) * 2 * page_tokens * hd: first the K block, then the V block.
+ *              Within a page, tokens are grouped in runs of 32 (t = 32 r + u).  K block element
+ *              (t, d): ((r * 2 + T) * (hd / 8) + d / 8) * 128 + R * 8 + d % 8 with T = (u / 4) % 2,
+ *              R = (u / 8) * 4 + u % 4.  V block element (t, d): page_tokens * hd offset, then
+ *              ((r * (hd / 16) + d / 16) * 4 + u / 8) * 128 + (d % 16) * 8 + u % 8.
+ *   page_table device int32 [n_seq, pages_per_seq]; ctx_len device int32 [n_seq] (0 = skip row)
+ *   out        device bf16 [n_seq, n_q_heads, hd]
+ *   workspace  device, at least pl_attention_workspace_bytes(...) bytes
+ * max_ctx bounds ctx_len (sizes the launch).  Positions at or beyond ctx_len inside the last page
+ * must hold finite values. */
+int64_t pl_attention_workspace_bytes(int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t hd,
+                                     int32_t max_ctx);
+int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page_table,
+                        const int32_t *ctx_len, void *out, void *workspace, int32_t n_seq,
+                        int32_t n_q_heads, int32_t n_kv_heads, int32_t hd, int32_t page_tokens,
+                        int32_t pages_per_seq, int32_t max_ctx, void *stream);
+/* Host helper: scatter fp32 [n, n_kv_heads, hd] keys and values of consecutive positions
+ * first_pos .. first_pos + n - 1 of one sequence into host images of its pages (same layout as
+ * above; `pages_host` is the host copy of the layer's pool, page ids taken from page_ids). */
+int pl_kv_pack_host(uint16_t *pages_host, const int32_t *page_ids, const float *k, const float *v,
+                    int32_t first_pos, int32_t n, int32_t n_kv_heads, int32_t hd, int32_t page_tokens);
+
+/* y = x W^T with bf16 inputs and fp32 accumulation.  x device bf16 [M, K]; w device bf16 [N, K];
+ * K a multiple of 64, N a multiple of 32, 1 <= M <= 512.
+ *   mode 0: y device fp32 [splits, M, N]; slice s holds the partial sum over K range s (their sum
+ *           over s is the product); splits >= 1 must divide K / 64.
+ *   mode 1: SwiGLU: w holds gate/up rows interleaved in blocks of 32 (see pl_weight_layout);
+ *           y device bf16 [M, N / 2] = silu(gate) * up; splits must be 1. */
+int pl_gemm_bf16(const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K,
+                 int32_t mode, int32_t splits, void *stream);
+
+/* Log-softmax + Gumbel-max sampler over fp32 logits (the decision is taken in fp32 with the
+ * operation order given in the sampler specification).  All arrays device memory:
+ * logits fp32 [n, vocab]; seq_id uint64 [n]; position int32 [n]; inv_temperature fp32 [n];
+ * forced int32 [n] (-1 = sample); token int32 [n] out; logprob fp32 [n] out; workspace at least
+ * pl_sample_workspace_bytes(n, vocab). */
+int64_t pl_sample_workspace_bytes(int32_t n, int32_t vocab);
+int pl_sample(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq_id,
+              const int32_t *position, const float *inv_temperature, const int32_t *forced,
+              uint64_t seed, int32_t *token, float *logprob, void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PL_H */

@@ -1,0 +1,208 @@
+// Ragged grouped-query decode attention over the paged bf16 KV cache (gfx950).
+//
+// One decode step of "generate next tokens" (Alg. 2 of the paper) attends one new query per
+// sequence over that sequence's whole cached history; the work is a stream of K and V bytes at a
+// few flops per byte, so the kernel is built around HBM reads: every load instruction of a
+// wavefront fetches one contiguous KiB that is already in MFMA operand order (the page layout is
+// chosen for that), the query heads that share a kv head ride along as the 16 columns of one
+// 16x16x32 MFMA so each K/V byte is read once for the whole group, and soft-max statistics are
+// reduced with cross-lane shuffles.  Work is split over (sequence, kv head, chunk of tokens);
+// chunks of one sequence are merged by a second kernel in a fixed order.
+#include "pl_common.h"
+
+namespace pl {
+namespace {
+
+__device__ inline float shfl_xor(float v, int mask) { return __shfl_xor(v, mask, 64); }
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
+  constexpr int NJ = HD / 32;   // QK MFMAs per 16-token tile
+  constexpr int NV = HD / 16;   // PV MFMAs per 32-token run
+  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int ctx = p.ctx_len[b];
+  const int t0 = c * p.chunk;
+  if (t0 >= ctx) return;
+  const int t1 = min(ctx, t0 + p.chunk);
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int head = l & 15, qg = l >> 4;
+  const int G = p.Hq / p.Hkv;
+  const int slot = p.row_slot ? p.row_slot[b] : b;
+  const int32_t *pt = p.page_table + (int64_t)slot * p.pages_per_seq;
+  const float scale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(hd)
+
+  // Query operand: column = head of the group (zero for the padding columns), k = head-dim slice.
+  bf16x8 qf[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    if (head < G) {
+      qf[j] = *(const bf16x8 *)(p.q + ((int64_t)b * p.Hq + g * G + head) * HD + j * 32 + qg * 8);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[j][e] = (__bf16)0.0f;
+    }
+  }
+
+  f32x4 o[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY, lsum = 0.f;
+
+  const int nblk = (t1 - t0 + 31) >> 5;
+  const int64_t page_elems = (int64_t)2 * p.page_tokens * HD;   // K block + V block of one kv head
+  auto run_base = [&](int blk) -> const bf16_t * {
+    int t = t0 + blk * 32;
+    int page = pt[t / p.page_tokens];
+    int r = (t % p.page_tokens) >> 5;
+    return p.kv + ((int64_t)page * p.Hkv + g) * page_elems + (int64_t)r * 32 * HD + l * 8;
+  };
+
+  bf16x8 kf[2][NJ], vf[NV];
+  auto load_run = [&](int blk) {
+    const bf16_t *kb = run_base(blk);
+    const bf16_t *vb = kb + (int64_t)p.page_tokens * HD;
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) kf[T][j] = *(const bf16x8 *)(kb + (T * NJ + j) * 512);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) vf[i] = *(const bf16x8 *)(vb + i * 512);
+  };
+
+  int blk = wave;
+  if (blk < nblk) load_run(blk);
+  while (blk < nblk) {
+    // scores of the 32 tokens of this run: two 16-token tiles
+    f32x4 s4[2];
+#pragma unroll
+    for (int T = 0; T < 2; ++T) {
+      s4[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        s4[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[T][j], qf[j], s4[T], 0, 0, 0);
+    }
+    bf16x8 vcur[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) vcur[i] = vf[i];
+    const int tbase = t0 + blk * 32 + qg * 8;
+    const int nxt = blk + 4;
+    if (nxt < nblk) load_run(nxt);   // next run's loads are in flight during the soft-max
+
+    float s[8];
+    float mb = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = s4[e >> 2][e & 3] * scale;
+      v = (tbase + e < t1) ? v : -INFINITY;
+      s[e] = v;
+      mb = fmaxf(mb, v);
+    }
+    mb = fmaxf(mb, shfl_xor(mb, 16));
+    mb = fmaxf(mb, shfl_xor(mb, 32));
+    const float m_new = fmaxf(m, mb);
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    float psum = 0.f;
+    bf16x8 pf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float pe = __builtin_amdgcn_exp2f(s[e] - m_new);
+      psum += pe;
+      pf[e] = (__bf16)pe;
+    }
+    lsum = lsum * alpha + psum;
+    m = m_new;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      o[i] *= alpha;
+      o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vcur[i], pf, o[i], 0, 0, 0);
+    }
+    blk = nxt;
+  }
+  lsum += shfl_xor(lsum, 16);
+  lsum += shfl_xor(lsum, 32);
+
+  // merge the four wavefronts of the workgroup
+  __shared__ float sm_o[4][16][HD];
+  __shared__ float sm_m[4][16], sm_l[4][16];
+  if (head < G) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sm_o[wave][head][i * 16 + qg * 4 + e] = o[i][e];
+    if (qg == 0) { sm_m[wave][head] = m; sm_l[wave][head] = lsum; }
+  }
+  __syncthreads();
+  const bool single = ctx <= p.chunk;
+  const int64_t pidx = ((int64_t)b * p.Hkv + g) * p.max_chunks + c;
+  for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
+    int h = idx / HD, d = idx % HD;
+    float M = fmaxf(fmaxf(sm_m[0][h], sm_m[1][h]), fmaxf(sm_m[2][h], sm_m[3][h]));
+    float L = 0.f, O = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      float f = __builtin_amdgcn_exp2f(sm_m[w][h] - M);
+      L += sm_l[w][h] * f;
+      O += sm_o[w][h][d] * f;
+    }
+    if (single) {
+      p.out[((int64_t)b * p.Hq + g * G + h) * HD + d] = (__bf16)(O / L);
+    } else {
+      p.part_o[(pidx * G + h) * HD + d] = O;
+      if (d == 0) { p.part_ml[(pidx * G + h) * 2] = M; p.part_ml[(pidx * G + h) * 2 + 1] = L; }
+    }
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_combine_kernel(AttnParams p) {
+  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+  const int ctx = p.ctx_len[b];
+  if (ctx <= p.chunk) return;   // empty rows and single-chunk rows were written by the first kernel
+  const int G = p.Hq / p.Hkv, g = hq / G, h = hq % G;
+  const int nchunk = (ctx + p.chunk - 1) / p.chunk;
+  const int64_t base = ((int64_t)b * p.Hkv + g) * p.max_chunks;
+  float M = -INFINITY;
+  for (int c = 0; c < nchunk; ++c) M = fmaxf(M, p.part_ml[((base + c) * G + h) * 2]);
+  float L = 0.f, O = 0.f;
+  for (int c = 0; c < nchunk; ++c) {
+    float f = __builtin_amdgcn_exp2f(p.part_ml[((base + c) * G + h) * 2] - M);
+    L += p.part_ml[((base + c) * G + h) * 2 + 1] * f;
+    O += p.part_o[((base + c) * G + h) * HD + d] * f;
+  }
+  p.out[((int64_t)b * p.Hq + hq) * HD + d] = (__bf16)(O / L);
+}
+
+}  // namespace
+
+int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx) {
+  // Tokens per workgroup: large enough that the merge is a small fraction of the bytes, small
+  // enough that a few hundred compute units all get work.  A function of the launch shape only,
+  // never of the contexts, so a sequence's result does not depend on its neighbours' lengths.
+  int chunk = 1024;
+  while (chunk > 128 && (int64_t)n_seq * Hkv * ((max_ctx + chunk - 1) / chunk) < 2048) chunk >>= 1;
+  return chunk;
+}
+
+int launch_attention(const AttnParams &p, hipStream_t s) {
+  if (p.n_seq <= 0) return 0;
+  dim3 grid(p.max_chunks, p.Hkv, p.n_seq), cgrid(p.Hq, p.n_seq);
+  switch (p.hd) {
+    case 128:
+      hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(128), 0, s, p);
+      break;
+    case 64:
+      hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p);
+      break;
+    case 32:
+      hipLaunchKernelGGL(attn_decode_kernel<32>, grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(32), 0, s, p);
+      break;
+    default:
+      return -1;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : -7;
+}
+
+}  // namespace pl

@@ -1,0 +1,165 @@
+// Small row-wise kernels of the decode step: token select + embedding gather + RMSNorm, residual
+// add (summing split-K partials) + RMSNorm, rotary tables, rotary + KV-cache append.
+#include "pl_common.h"
+
+namespace pl {
+namespace {
+
+__device__ inline float block_sum_256(float v) {
+  __shared__ float red[4];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+// h[row] = E[token]; a[row] = rmsnorm(h[row]) * g.  token = input_tok[row] if >= 0, else the token
+// the previous step produced for this row's slot.
+__global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const bf16_t *embed, const bf16_t *g,
+                                                            const int32_t *input_tok, const int32_t *last_tok,
+                                                            const int32_t *row_slot, float *h, bf16_t *a,
+                                                            int d, int vocab, float eps) {
+  const int row = blockIdx.x;
+  int tok = input_tok[row];
+  if (tok < 0 && last_tok) tok = last_tok[row_slot[row]];
+  tok = min(max(tok, 0), vocab - 1);
+  const bf16_t *e = embed + (int64_t)tok * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = (float)e[i];
+    h[(int64_t)row * d + i] = v;
+    ss += v * v;
+  }
+  ss = block_sum_256(ss);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256)
+    a[(int64_t)row * d + i] = (__bf16)(h[(int64_t)row * d + i] * r * (float)g[i]);
+}
+
+// h[row] += sum_s parts[s][row]; a[row] = rmsnorm(h[row]) * g.  Partials are added in slice order.
+__global__ __launch_bounds__(256) void resid_rmsnorm_kernel(float *h, const float *parts, int splits,
+                                                            const bf16_t *g, bf16_t *a, int n, int d, float eps) {
+  const int row = blockIdx.x;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = h[(int64_t)row * d + i];
+    for (int s = 0; s < splits; ++s) v += parts[((int64_t)s * n + row) * d + i];
+    h[(int64_t)row * d + i] = v;
+    ss += v * v;
+  }
+  ss = block_sum_256(ss);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256)
+    a[(int64_t)row * d + i] = (__bf16)(h[(int64_t)row * d + i] * r * (float)g[i]);
+}
+
+// cos/sin of pos * theta^(-2i/hd), evaluated in double so long positions lose nothing; also the
+// attention length of the step (pos + 1).
+__global__ void rope_tables_kernel(const int32_t *pos, float *cs, int32_t *ctx_len, int n, int hd, float theta) {
+  const int half = hd / 2;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n * half) return;
+  const int row = idx / half, i = idx % half;
+  const double inv_freq = pow((double)theta, -2.0 * (double)i / (double)hd);
+  const double ang = (double)pos[row] * inv_freq;
+  cs[(int64_t)row * hd + i] = (float)cos(ang);
+  cs[(int64_t)row * hd + half + i] = (float)sin(ang);
+  if (i == 0) ctx_len[row] = pos[row] + 1;
+}
+
+// qkv (fp32, split-K partials) -> rotated q (bf16), rotated k and v into the row's cache page.
+__global__ __launch_bounds__(256) void rope_append_kernel(const float *qkv, int splits, const float *cs,
+                                                          const int32_t *pos, const int32_t *row_slot,
+                                                          const int32_t *page_table, bf16_t *q_out,
+                                                          bf16_t *kv_layer, int n, int Hq, int Hkv, int hd,
+                                                          int page_tokens, int pages_per_seq) {
+  const int row = blockIdx.x;
+  const int half = hd / 2;
+  const int width = (Hq + 2 * Hkv) * hd;
+  const int p = pos[row];
+  const int page = page_table[(int64_t)row_slot[row] * pages_per_seq + p / page_tokens];
+  const int t = p % page_tokens;
+  const float *c = cs + (int64_t)row * hd, *sn = c + half;
+  auto val = [&](int col) {
+    float v = 0.f;
+    for (int s = 0; s < splits; ++s) v += qkv[((int64_t)s * n + row) * width + col];
+    return v;
+  };
+  const int64_t page_elems = (int64_t)2 * page_tokens * hd;
+  // rotated pairs of the q and k heads
+  for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += 256) {
+    const int hh = idx / half, i = idx % half;
+    const float x1 = val(hh * hd + i), x2 = val(hh * hd + half + i);
+    const float y1 = x1 * c[i] - x2 * sn[i], y2 = x2 * c[i] + x1 * sn[i];
+    if (hh < Hq) {
+      bf16_t *q = q_out + ((int64_t)row * Hq + hh) * hd;
+      q[i] = (__bf16)y1;
+      q[half + i] = (__bf16)y2;
+    } else {
+      bf16_t *kb = kv_layer + ((int64_t)page * Hkv + (hh - Hq)) * page_elems;
+      kb[k_elem_offset(t, i, hd)] = (__bf16)y1;
+      kb[k_elem_offset(t, half + i, hd)] = (__bf16)y2;
+    }
+  }
+  for (int idx = threadIdx.x; idx < Hkv * hd; idx += 256) {
+    const int g = idx / hd, dd = idx % hd;
+    bf16_t *vb = kv_layer + ((int64_t)page * Hkv + g) * page_elems + (int64_t)page_tokens * hd;
+    vb[v_elem_offset(t, dd, hd)] = (__bf16)val((Hq + Hkv) * hd + idx);
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+}  // namespace
+
+static inline int ok() { return hipGetLastError() == hipSuccess ? 0 : -7; }
+
+int launch_embed_rmsnorm(const bf16_t *embed, const bf16_t *g, const int32_t *input_tok,
+                         const int32_t *last_tok, const int32_t *row_slot, float *h, bf16_t *a, int n,
+                         int d, int vocab, float eps, hipStream_t s) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(embed_rmsnorm_kernel, dim3(n), dim3(256), 0, s, embed, g, input_tok, last_tok, row_slot,
+                     h, a, d, vocab, eps);
+  return ok();
+}
+
+int launch_resid_rmsnorm(float *h, const float *parts, int splits, const bf16_t *g, bf16_t *a, int n, int d,
+                         float eps, hipStream_t s) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(resid_rmsnorm_kernel, dim3(n), dim3(256), 0, s, h, parts, splits, g, a, n, d, eps);
+  return ok();
+}
+
+int launch_rope_tables(const int32_t *pos, float *cs, int32_t *ctx_len, int n, int hd, float theta,
+                       hipStream_t s) {
+  if (n <= 0) return 0;
+  int total = n * (hd / 2);
+  hipLaunchKernelGGL(rope_tables_kernel, dim3((total + 255) / 256), dim3(256), 0, s, pos, cs, ctx_len, n, hd,
+                     theta);
+  return ok();
+}
+
+int launch_rope_append(const float *qkv, int splits, const float *cs, const int32_t *pos,
+                       const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out, bf16_t *kv_layer,
+                       int n, int Hq, int Hkv, int hd, int page_tokens, int pages_per_seq, hipStream_t s) {
+  if (n <= 0) return 0;
+  hipLaunchKernelGGL(rope_append_kernel, dim3(n), dim3(256), 0, s, qkv, splits, cs, pos, row_slot, page_table,
+                     q_out, kv_layer, n, Hq, Hkv, hd, page_tokens, pages_per_seq);
+  return ok();
+}
+
+int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s) {
+  if (n <= 0) return 0;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, v, n);
+  return ok();
+}
+
+}  // namespace pl

@@ -1,0 +1,775 @@
+// Host side of the decode engine: slot table, KV page allocator, weight-buffer manager, step driver,
+// and the extern "C" boundary declared in include/pl.h.
+//
+// The engine is the generation half of the Actor loop (Alg. 2 of the paper): a constant batch of
+// slots, one token per occupied slot per step, refill through add/retire, and weight updates that
+// are staged on a side stream and become active only between two steps while every sequence keeps
+// its key/value pages (Sec. 5.1).
+#include "../../include/pl.h"
+#include "pl_common.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                       \
+  do {                                                                                      \
+    hipError_t _e = (expr);                                                                 \
+    if (_e != hipSuccess) return fail(PL_E_HIP, "%s: %s", #expr, hipGetErrorString(_e));    \
+  } while (0)
+
+inline uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+inline float bf16_bits_to_f32(uint16_t b) {
+  uint32_t u = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+struct Tensor {
+  std::string name;
+  int64_t offset, rows, cols;
+};
+
+struct Seq {
+  bool active = false;
+  uint64_t seq_id = 0;
+  std::vector<int32_t> prompt;
+  int32_t n_prompt = 0, max_new = 0, pos = 0, n_emitted = 0, next_input = -1;
+  float inv_t = 1.f;
+  std::vector<int32_t> pages;
+};
+
+struct LayerW {
+  const bf16_t *g1, *w_qkv, *w_o, *g2, *w_gu, *w_d;
+};
+
+}  // namespace
+
+struct pl_engine {
+  pl_model_cfg cfg{};
+  bool dry = false;
+  int G = 1, page_tokens = 64, pages_per_seq = 0;
+  int64_t n_pages = 0, layer_stride = 0, page_stride = 0;   // elements
+  // weights
+  std::vector<Tensor> layout;
+  int64_t blob_elems = 0;
+  bf16_t *wbuf[2] = {nullptr, nullptr};
+  int active_buf = 0;
+  uint32_t version = 0;
+  bool loaded = false;
+  bool staged = false, staged_wait = false;
+  uint32_t staged_version = 0;
+  hipEvent_t ev_staged = nullptr, ev_copy0 = nullptr;
+  // kv
+  bf16_t *kv_pool = nullptr;
+  std::vector<int32_t> free_pages;
+  int32_t *pt_h = nullptr, *pt_d = nullptr;
+  bool pt_dirty = false;
+  std::vector<Seq> seqs;
+  // per-step metadata: host (pinned) and device images, same layout
+  char *meta_h = nullptr, *meta_d = nullptr;
+  int64_t meta_bytes = 0;
+  // work buffers
+  float *h = nullptr, *parts = nullptr, *logits = nullptr, *cs = nullptr, *attn_po = nullptr, *attn_pml = nullptr;
+  bf16_t *a = nullptr, *q_rot = nullptr, *attn_out = nullptr, *mid = nullptr;
+  int32_t *ctx_len = nullptr, *tok_d = nullptr;
+  float *lp_d = nullptr;
+  void *samp_ws = nullptr;
+  int32_t *tok_h = nullptr;
+  float *lp_h = nullptr;
+  int attn_chunk = 1024, attn_max_chunks = 1;
+  int sp_qkv = 1, sp_o = 1, sp_d = 1;
+  hipStream_t s_dec = nullptr, s_copy = nullptr;
+  hipEvent_t ev_a = nullptr, ev_b = nullptr, ev_c = nullptr;
+  // last step
+  int last_n = 0;
+  pl_stats st{};
+  int64_t streamed_weight_bytes = 0;
+
+  int32_t *m_row_slot(bool dev) { return (int32_t *)(dev ? meta_d : meta_h); }
+  int32_t *m_pos(bool dev) { return m_row_slot(dev) + cfg.max_batch; }
+  int32_t *m_input(bool dev) { return m_pos(dev) + cfg.max_batch; }
+  int32_t *m_forced(bool dev) { return m_input(dev) + cfg.max_batch; }
+  float *m_inv_t(bool dev) { return (float *)(m_forced(dev) + cfg.max_batch); }
+  uint64_t *m_seq_id(bool dev) { return (uint64_t *)(m_inv_t(dev) + cfg.max_batch); }
+
+  const bf16_t *wptr(int buf, const char *name) const {
+    for (auto &t : layout)
+      if (t.name == name) return wbuf[buf] + t.offset;
+    return nullptr;
+  }
+};
+
+namespace {
+
+void build_layout(pl_engine *e) {
+  const pl_model_cfg &c = e->cfg;
+  int64_t off = 0;
+  auto add = [&](const std::string &n, int64_t r, int64_t cc) {
+    e->layout.push_back(Tensor{n, off, r, cc});
+    off += r * cc;
+  };
+  const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
+  add("embed", c.vocab, d);
+  for (int l = 0; l < c.n_layers; ++l) {
+    std::string p = "l" + std::to_string(l) + ".";
+    add(p + "g1", d, 1);
+    add(p + "w_qkv", qd + 2 * kvd, d);
+    add(p + "w_o", d, qd);
+    add(p + "g2", d, 1);
+    add(p + "w_gu", 2 * (int64_t)c.d_ffn, d);
+    add(p + "w_d", d, c.d_ffn);
+  }
+  add("gf", d, 1);
+  add("lm_head", c.vocab, d);
+  e->blob_elems = off;
+  e->streamed_weight_bytes = 2 * (off - (int64_t)c.vocab * d);
+}
+
+int check_cfg(const pl_model_cfg &c) {
+  if (c.n_layers < 0 || c.d_model <= 0 || c.n_q_heads <= 0 || c.n_kv_heads <= 0 || c.d_ffn <= 0 || c.vocab <= 0)
+    return fail(PL_E_INVAL, "non-positive model dimension");
+  if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128) return fail(PL_E_INVAL, "head_dim must be 32, 64 or 128");
+  if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 16)
+    return fail(PL_E_INVAL, "n_q_heads must be a multiple of n_kv_heads with at most 16 query heads per kv head");
+  if (c.d_model % 64 || c.d_ffn % 64 || (c.n_q_heads * c.head_dim) % 64)
+    return fail(PL_E_INVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 64");
+  if (c.vocab % 32) return fail(PL_E_INVAL, "vocab must be a multiple of 32");
+  if (c.max_batch < 1 || c.max_batch > 512) return fail(PL_E_INVAL, "max_batch must be in [1, 512]");
+  if (c.max_context < 1) return fail(PL_E_INVAL, "max_context must be positive");
+  if (c.kv_page_tokens < 0 || c.kv_page_tokens % 32) return fail(PL_E_INVAL, "kv_page_tokens must be a multiple of 32");
+  if (c.n_weight_buffers != 1 && c.n_weight_buffers != 2) return fail(PL_E_INVAL, "n_weight_buffers must be 1 or 2");
+  if (!(c.rope_theta > 0) || !(c.rms_eps >= 0)) return fail(PL_E_INVAL, "bad rope_theta / rms_eps");
+  return PL_OK;
+}
+
+template <typename T>
+int dev_alloc(T **p, int64_t n_elems) {
+  if (n_elems <= 0) n_elems = 1;
+  hipError_t err = hipMalloc((void **)p, (size_t)n_elems * sizeof(T));
+  if (err != hipSuccess) return fail(PL_E_NOMEM, "hipMalloc of %lld bytes failed: %s", (long long)(n_elems * sizeof(T)), hipGetErrorString(err));
+  return PL_OK;
+}
+
+int alloc_device(pl_engine *e) {
+  const pl_model_cfg &c = e->cfg;
+  HIP_TRY(hipSetDevice(c.device));
+  HIP_TRY(hipStreamCreateWithFlags(&e->s_dec, hipStreamNonBlocking));
+  HIP_TRY(hipStreamCreateWithFlags(&e->s_copy, hipStreamNonBlocking));
+  HIP_TRY(hipEventCreate(&e->ev_a));
+  HIP_TRY(hipEventCreate(&e->ev_b));
+  HIP_TRY(hipEventCreate(&e->ev_c));
+  HIP_TRY(hipEventCreate(&e->ev_staged));
+  HIP_TRY(hipEventCreate(&e->ev_copy0));
+  int rc;
+  for (int b = 0; b < c.n_weight_buffers; ++b)
+    if ((rc = dev_alloc(&e->wbuf[b], e->blob_elems))) return rc;
+  const int64_t pool_elems = e->layer_stride * c.n_layers;
+  if ((rc = dev_alloc(&e->kv_pool, pool_elems))) return rc;
+  // Every position a kernel may touch must hold a finite value: masked soft-max weights are
+  // exactly 0, and 0 * finite stays 0.
+  HIP_TRY(hipMemsetAsync(e->kv_pool, 0, (size_t)pool_elems * 2, e->s_dec));
+  const int B = c.max_batch;
+  const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
+  const int64_t wq = qd + 2 * kvd;
+  e->sp_qkv = pl::gemm_pick_splits(B, (int)wq, (int)d);
+  e->sp_o = pl::gemm_pick_splits(B, (int)d, (int)qd);
+  e->sp_d = pl::gemm_pick_splits(B, (int)d, c.d_ffn);
+  int64_t parts = std::max(std::max(e->sp_qkv * wq, e->sp_o * d), e->sp_d * d) * B;
+  if ((rc = dev_alloc(&e->pt_d, (int64_t)B * e->pages_per_seq))) return rc;
+  if ((rc = dev_alloc(&e->meta_d, e->meta_bytes))) return rc;
+  if ((rc = dev_alloc(&e->h, B * d))) return rc;
+  if ((rc = dev_alloc(&e->a, B * d))) return rc;
+  if ((rc = dev_alloc(&e->parts, parts))) return rc;
+  if ((rc = dev_alloc(&e->q_rot, B * qd))) return rc;
+  if ((rc = dev_alloc(&e->attn_out, B * qd))) return rc;
+  if ((rc = dev_alloc(&e->mid, (int64_t)B * c.d_ffn))) return rc;
+  if ((rc = dev_alloc(&e->logits, (int64_t)B * c.vocab))) return rc;
+  if ((rc = dev_alloc(&e->cs, (int64_t)B * c.head_dim))) return rc;
+  if ((rc = dev_alloc(&e->ctx_len, B))) return rc;
+  if ((rc = dev_alloc(&e->tok_d, B))) return rc;
+  if ((rc = dev_alloc(&e->lp_d, B))) return rc;
+  e->attn_chunk = pl::attention_chunk_tokens(B, c.n_kv_heads, c.max_context);
+  e->attn_max_chunks = (c.max_context + e->attn_chunk - 1) / e->attn_chunk;
+  const int64_t np = (int64_t)B * c.n_kv_heads * e->attn_max_chunks * e->G;
+  if ((rc = dev_alloc(&e->attn_po, np * c.head_dim))) return rc;
+  if ((rc = dev_alloc(&e->attn_pml, np * 2))) return rc;
+  char *ws = nullptr;
+  if ((rc = dev_alloc(&ws, pl::sample_workspace_bytes(B, c.vocab)))) return rc;
+  e->samp_ws = ws;
+  HIP_TRY(hipHostMalloc((void **)&e->pt_h, (size_t)B * e->pages_per_seq * 4, hipHostMallocDefault));
+  HIP_TRY(hipHostMalloc((void **)&e->meta_h, (size_t)e->meta_bytes, hipHostMallocDefault));
+  HIP_TRY(hipHostMalloc((void **)&e->tok_h, (size_t)B * 4, hipHostMallocDefault));
+  HIP_TRY(hipHostMalloc((void **)&e->lp_h, (size_t)B * 4, hipHostMallocDefault));
+  memset(e->pt_h, 0, (size_t)B * e->pages_per_seq * 4);
+  HIP_TRY(hipStreamSynchronize(e->s_dec));
+  return PL_OK;
+}
+
+LayerW layer_weights(const pl_engine *e, int l) {
+  const bf16_t *base = e->wbuf[e->active_buf];
+  const Tensor *t = &e->layout[1 + (size_t)l * 6];
+  return LayerW{base + t[0].offset, base + t[1].offset, base + t[2].offset,
+                base + t[3].offset, base + t[4].offset, base + t[5].offset};
+}
+
+// The fixed kernel sequence of one decode step over n rows (rows = occupied slots, slot order).
+int enqueue_step(pl_engine *e, int n) {
+  const pl_model_cfg &c = e->cfg;
+  hipStream_t s = e->s_dec;
+  const bf16_t *base = e->wbuf[e->active_buf];
+  const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, wq = qd + 2 * kvd;
+  const bf16_t *embed = base + e->layout.front().offset;
+  const bf16_t *gf = base + e->layout[e->layout.size() - 2].offset;
+  const bf16_t *lm = base + e->layout.back().offset;
+  int rc = 0;
+  rc |= pl::launch_rope_tables(e->m_pos(true), e->cs, e->ctx_len, n, c.head_dim, c.rope_theta, s);
+  const bf16_t *g_first = c.n_layers ? layer_weights(e, 0).g1 : gf;
+  rc |= pl::launch_embed_rmsnorm(embed, g_first, e->m_input(true), nullptr, e->m_row_slot(true), e->h, e->a, n,
+                                 d, c.vocab, c.rms_eps, s);
+  for (int l = 0; l < c.n_layers && !rc; ++l) {
+    const LayerW w = layer_weights(e, l);
+    bf16_t *kv_layer = e->kv_pool + (int64_t)l * e->layer_stride;
+    rc |= pl::launch_gemm(e->a, w.w_qkv, e->parts, n, wq, d, 0, e->sp_qkv, s);
+    rc |= pl::launch_rope_append(e->parts, e->sp_qkv, e->cs, e->m_pos(true), e->m_row_slot(true), e->pt_d,
+                                 e->q_rot, kv_layer, n, c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens,
+                                 e->pages_per_seq, s);
+    pl::AttnParams ap{};
+    ap.q = e->q_rot; ap.kv = kv_layer; ap.page_table = e->pt_d; ap.ctx_len = e->ctx_len;
+    ap.row_slot = e->m_row_slot(true); ap.out = e->attn_out; ap.part_o = e->attn_po; ap.part_ml = e->attn_pml;
+    ap.n_seq = n; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.hd = c.head_dim;
+    ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
+    ap.max_chunks = e->attn_max_chunks;
+    rc |= pl::launch_attention(ap, s);
+    rc |= pl::launch_gemm(e->attn_out, w.w_o, e->parts, n, d, qd, 0, e->sp_o, s);
+    rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_o, w.g2, e->a, n, d, c.rms_eps, s);
+    rc |= pl::launch_gemm(e->a, w.w_gu, e->mid, n, 2 * c.d_ffn, d, 1, 1, s);
+    rc |= pl::launch_gemm(e->mid, w.w_d, e->parts, n, d, c.d_ffn, 0, e->sp_d, s);
+    const bf16_t *g_next = (l + 1 < c.n_layers) ? layer_weights(e, l + 1).g1 : gf;
+    rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_d, g_next, e->a, n, d, c.rms_eps, s);
+  }
+  rc |= pl::launch_gemm(e->a, lm, e->logits, n, c.vocab, d, 0, 1, s);
+  pl::SampleParams sp{};
+  sp.logits = e->logits; sp.n = n; sp.vocab = c.vocab; sp.seq_id = e->m_seq_id(true);
+  sp.position = e->m_pos(true); sp.inv_t = e->m_inv_t(true); sp.forced = e->m_forced(true);
+  sp.seed = c.seed; sp.token = e->tok_d; sp.logprob = e->lp_d; sp.workspace = e->samp_ws;
+  sp.last_tok = nullptr; sp.row_slot = nullptr;
+  rc |= pl::launch_sample(sp, s);
+  return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
+}
+
+void activate_staged(pl_engine *e) {
+  if (e->cfg.n_weight_buffers == 2) e->active_buf ^= 1;
+  e->version = e->staged_version;
+  e->staged = false;
+  e->st.swaps++;
+}
+
+int admit(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt, int32_t max_new, float temp,
+          int32_t context_len, int32_t n_emitted, int32_t last_token, int32_t *out_slot) {
+  const pl_model_cfg &c = e->cfg;
+  if (n_prompt < 1 || max_new < 1 || !(temp > 0.f) || !std::isfinite(temp))
+    return fail(PL_E_INVAL, "need n_prompt >= 1, max_new >= 1, temperature > 0");
+  if ((int64_t)n_prompt + max_new - 1 > c.max_context) return fail(PL_E_CTX, "n_prompt + max_new - 1 exceeds max_context");
+  const bool need_prompt = context_len < n_prompt;
+  if (need_prompt && !prompt) return fail(PL_E_INVAL, "prompt is NULL");
+  if (context_len < 0 || context_len > n_prompt + max_new - 1 || n_emitted < 0 || n_emitted >= max_new)
+    return fail(PL_E_INVAL, "inconsistent context_len / n_emitted");
+  if (prompt)
+    for (int i = 0; i < n_prompt; ++i)
+      if (prompt[i] < 0 || prompt[i] >= c.vocab) return fail(PL_E_INVAL, "prompt token %d out of range", prompt[i]);
+  if (context_len >= n_prompt && (last_token < 0 || last_token >= c.vocab)) return fail(PL_E_INVAL, "last_token out of range");
+  int slot = -1;
+  for (int i = 0; i < c.max_batch; ++i)
+    if (!e->seqs[i].active) { slot = i; break; }
+  if (slot < 0) return fail(PL_E_NOSLOT, "all %d slots are occupied", c.max_batch);
+  // pages for what is already cached (or, for a fresh sequence, for its prompt)
+  const int64_t need_tok = std::max<int64_t>(context_len, n_prompt);
+  const int64_t want_pages = (need_tok + e->page_tokens - 1) / e->page_tokens;
+  const int64_t need_pages = want_pages;
+  if ((int64_t)e->free_pages.size() < want_pages) return fail(PL_E_NOKV, "KV pool cannot hold the prompt (%lld pages free)", (long long)e->free_pages.size());
+  Seq &q = e->seqs[slot];
+  q = Seq{};
+  q.active = true;
+  q.seq_id = seq_id;
+  if (prompt) q.prompt.assign(prompt, prompt + n_prompt);
+  q.n_prompt = n_prompt;
+  q.max_new = max_new;
+  q.inv_t = 1.0f / temp;
+  q.pos = context_len;
+  q.n_emitted = n_emitted;
+  q.next_input = last_token;
+  for (int64_t i = 0; i < need_pages; ++i) {
+    q.pages.push_back(e->free_pages.back());
+    e->free_pages.pop_back();
+    if (e->pt_h) e->pt_h[(int64_t)slot * e->pages_per_seq + i] = q.pages.back();
+  }
+  e->pt_dirty = true;
+  if (out_slot) *out_slot = slot;
+  return PL_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char *pl_last_error(void) { return g_err; }
+
+int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
+  if (!cfg || !out) return fail(PL_E_INVAL, "NULL argument");
+  *out = nullptr;
+  int rc = check_cfg(*cfg);
+  if (rc) return rc;
+  pl_engine *e = new (std::nothrow) pl_engine();
+  if (!e) return fail(PL_E_NOMEM, "out of host memory");
+  e->cfg = *cfg;
+  e->dry = cfg->device == PL_DEVICE_NONE;
+  e->G = cfg->n_q_heads / cfg->n_kv_heads;
+  e->page_tokens = cfg->kv_page_tokens ? cfg->kv_page_tokens : 64;
+  e->pages_per_seq = (cfg->max_context + e->page_tokens - 1) / e->page_tokens;
+  e->n_pages = cfg->kv_pool_tokens / e->page_tokens;
+  if (e->n_pages < 1 || e->n_pages > 0x7FFFFFFF) {
+    delete e;
+    return fail(PL_E_INVAL, "kv_pool_tokens must hold at least one page");
+  }
+  e->page_stride = (int64_t)cfg->n_kv_heads * 2 * e->page_tokens * cfg->head_dim;
+  e->layer_stride = e->page_stride * e->n_pages;
+  build_layout(e);
+  e->seqs.resize(cfg->max_batch);
+  e->free_pages.reserve(e->n_pages);
+  for (int64_t p = e->n_pages - 1; p >= 0; --p) e->free_pages.push_back((int32_t)p);   // page 0 is handed out first
+  e->meta_bytes = (int64_t)cfg->max_batch * (4 * 5 + 8);
+  e->st.kv_pages_total = e->n_pages;
+  if (e->dry) {
+    e->meta_h = (char *)calloc(1, (size_t)e->meta_bytes);
+    if (!e->meta_h) { delete e; return fail(PL_E_NOMEM, "out of host memory"); }
+  } else {
+    if (cfg->device < 0) { delete e; return fail(PL_E_INVAL, "bad device"); }
+    rc = alloc_device(e);
+    if (rc) { pl_destroy(e); return rc; }
+  }
+  *out = e;
+  return PL_OK;
+}
+
+void pl_destroy(pl_engine *e) {
+  if (!e) return;
+  if (e->dry) {
+    free(e->meta_h);
+  } else {
+    (void)hipSetDevice(e->cfg.device);
+    if (e->s_dec) (void)hipStreamSynchronize(e->s_dec);
+    if (e->s_copy) (void)hipStreamSynchronize(e->s_copy);
+    void *dev[] = {e->wbuf[0], e->wbuf[1], e->kv_pool, e->pt_d, e->meta_d, e->h, e->a, e->parts, e->q_rot,
+                   e->attn_out, e->mid, e->logits, e->cs, e->ctx_len, e->tok_d, e->lp_d, e->attn_po,
+                   e->attn_pml, e->samp_ws};
+    for (void *p : dev)
+      if (p) (void)hipFree(p);
+    void *hst[] = {e->pt_h, e->meta_h, e->tok_h, e->lp_h};
+    for (void *p : hst)
+      if (p) (void)hipHostFree(p);
+    hipEvent_t evs[] = {e->ev_a, e->ev_b, e->ev_c, e->ev_staged, e->ev_copy0};
+    for (hipEvent_t ev : evs)
+      if (ev) (void)hipEventDestroy(ev);
+    if (e->s_dec) (void)hipStreamDestroy(e->s_dec);
+    if (e->s_copy) (void)hipStreamDestroy(e->s_copy);
+  }
+  delete e;
+}
+
+int32_t pl_weight_count(const pl_engine *e) { return e ? (int32_t)e->layout.size() : 0; }
+
+int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t *offset_elems, int64_t shape[2]) {
+  if (!e || idx < 0 || idx >= (int32_t)e->layout.size()) return fail(PL_E_INVAL, "tensor index out of range");
+  const Tensor &t = e->layout[idx];
+  if (name) *name = t.name.c_str();
+  if (offset_elems) *offset_elems = t.offset;
+  if (shape) { shape[0] = t.rows; shape[1] = t.cols; }
+  return PL_OK;
+}
+
+int64_t pl_weight_nbytes(const pl_engine *e) { return e ? e->blob_elems * 2 : 0; }
+
+int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes) {
+  if (!e || !src) return fail(PL_E_INVAL, "NULL argument");
+  if (nbytes != e->blob_elems * 2) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * 2));
+  if (e->staged) return fail(PL_E_BUSY, "a weight update is staged");
+  if (!e->dry) {
+    HIP_TRY(hipSetDevice(e->cfg.device));
+    HIP_TRY(hipStreamSynchronize(e->s_dec));
+    HIP_TRY(hipMemcpy(e->wbuf[e->active_buf], src, (size_t)nbytes, hipMemcpyDefault));
+  }
+  if (e->loaded) { e->version++; e->st.swaps++; }
+  e->loaded = true;
+  return PL_OK;
+}
+
+int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flags, uint32_t *out_new_version) {
+  if (!e || !src) return fail(PL_E_INVAL, "NULL argument");
+  if (flags != PL_SWAP_ASYNC && flags != PL_SWAP_WAIT) return fail(PL_E_INVAL, "unknown flags");
+  if (nbytes != e->blob_elems * 2) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * 2));
+  if (!e->loaded) return fail(PL_E_STATE, "no weights loaded yet");
+  if (e->staged) return fail(PL_E_BUSY, "the previous weight update is not active yet");
+  e->staged_version = e->version + 1;
+  e->staged_wait = (flags == PL_SWAP_WAIT);
+  if (!e->dry) {
+    HIP_TRY(hipSetDevice(e->cfg.device));
+    if (e->cfg.n_weight_buffers == 2) {
+      // Steps are synchronous, so no kernel is reading the inactive buffer now.
+      HIP_TRY(hipEventRecord(e->ev_copy0, e->s_copy));
+      HIP_TRY(hipMemcpyAsync(e->wbuf[e->active_buf ^ 1], src, (size_t)nbytes, hipMemcpyDefault, e->s_copy));
+      HIP_TRY(hipEventRecord(e->ev_staged, e->s_copy));
+    } else {
+      HIP_TRY(hipEventRecord(e->ev_copy0, e->s_dec));
+      HIP_TRY(hipMemcpyAsync(e->wbuf[0], src, (size_t)nbytes, hipMemcpyDefault, e->s_dec));
+      HIP_TRY(hipEventRecord(e->ev_staged, e->s_dec));
+      HIP_TRY(hipStreamSynchronize(e->s_dec));
+      e->staged_wait = true;
+    }
+  }
+  e->staged = true;
+  if (out_new_version) *out_new_version = e->staged_version;
+  return PL_OK;
+}
+
+int pl_swap_poll(pl_engine *e, int32_t *staged_ready, uint32_t *active_version) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  int ready = 0;
+  if (e->staged) {
+    if (e->dry) ready = 1;
+    else {
+      hipError_t q = hipEventQuery(e->ev_staged);
+      if (q == hipSuccess) ready = 1;
+      else if (q != hipErrorNotReady) return fail(PL_E_HIP, "hipEventQuery: %s", hipGetErrorString(q));
+    }
+  }
+  if (staged_ready) *staged_ready = ready;
+  if (active_version) *active_version = e->version;
+  return PL_OK;
+}
+
+int pl_add_sequence(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt, int32_t max_new,
+                    float temperature, int32_t *out_slot) {
+  if (!e || !prompt) return fail(PL_E_INVAL, "NULL argument");
+  return admit(e, seq_id, prompt, n_prompt, max_new, temperature, 0, 0, -1, out_slot);
+}
+
+int pl_debug_add_sequence_at(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt, int32_t max_new,
+                             float temperature, int32_t context_len, int32_t n_emitted, int32_t last_token,
+                             int32_t *out_slot) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  return admit(e, seq_id, prompt, n_prompt, max_new, temperature, context_len, n_emitted, last_token, out_slot);
+}
+
+int pl_retire_sequence(pl_engine *e, int32_t slot) {
+  if (!e || slot < 0 || slot >= e->cfg.max_batch) return fail(PL_E_INVAL, "slot out of range");
+  Seq &q = e->seqs[slot];
+  if (!q.active) return fail(PL_E_STATE, "slot %d is idle", slot);
+  for (int32_t p : q.pages) e->free_pages.push_back(p);
+  q = Seq{};
+  return PL_OK;
+}
+
+int32_t pl_num_active(const pl_engine *e) {
+  int n = 0;
+  if (e)
+    for (auto &q : e->seqs) n += q.active;
+  return n;
+}
+
+int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
+  if (!e || !out) return fail(PL_E_INVAL, "NULL argument");
+  if (!e->loaded) return fail(PL_E_STATE, "no weights loaded");
+  const pl_model_cfg &c = e->cfg;
+  // 1. validate: nothing below may fail half-way
+  int n = 0;
+  int64_t new_pages = 0;
+  for (int s = 0; s < c.max_batch; ++s) {
+    const Seq &q = e->seqs[s];
+    if (!q.active) continue;
+    if (q.n_emitted >= q.max_new) return fail(PL_E_STATE, "slot %d has finished; retire it", s);
+    if (q.pos >= c.max_context) return fail(PL_E_CTX, "slot %d is at max_context", s);
+    if (forced && forced[s] >= c.vocab) return fail(PL_E_INVAL, "forced token out of range");
+    if (q.pos / e->page_tokens >= (int)q.pages.size()) ++new_pages;
+    ++n;
+  }
+  if (new_pages > (int64_t)e->free_pages.size()) return fail(PL_E_NOKV, "KV pool exhausted: %lld pages needed, %lld free", (long long)new_pages, (long long)e->free_pages.size());
+  out->n = n;
+  out->step_ms = 0.f;
+  out->swap_stall_ms = 0.f;
+  e->last_n = n;
+  if (n == 0) return PL_OK;
+
+  // 2. in-flight weight update: flips only here, between two steps
+  bool timed_stall = false;
+  if (e->staged) {
+    if (e->dry) {
+      activate_staged(e);
+    } else if (e->staged_wait) {
+      HIP_TRY(hipEventRecord(e->ev_c, e->s_dec));
+      HIP_TRY(hipStreamWaitEvent(e->s_dec, e->ev_staged, 0));
+      timed_stall = true;
+      activate_staged(e);
+    } else {
+      hipError_t qy = hipEventQuery(e->ev_staged);
+      if (qy == hipSuccess) activate_staged(e);
+      else if (qy != hipErrorNotReady) return fail(PL_E_HIP, "hipEventQuery: %s", hipGetErrorString(qy));
+    }
+    if (!e->staged && !e->dry) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, e->ev_copy0, e->ev_staged) == hipSuccess) e->st.last_swap_copy_ms = ms;
+      (void)hipGetLastError();
+    }
+  }
+
+  // 3. pages and per-step metadata
+  int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
+  float *inv_t = e->m_inv_t(false);
+  uint64_t *sid = e->m_seq_id(false);
+  int r = 0;
+  double kv_tokens = 0;
+  for (int s = 0; s < c.max_batch; ++s) {
+    Seq &q = e->seqs[s];
+    if (!q.active) continue;
+    if (q.pos / e->page_tokens >= (int)q.pages.size()) {
+      q.pages.push_back(e->free_pages.back());
+      e->free_pages.pop_back();
+      if (e->pt_h) e->pt_h[(int64_t)s * e->pages_per_seq + q.pages.size() - 1] = q.pages.back();
+      e->pt_dirty = true;
+    }
+    row_slot[r] = s;
+    pos[r] = q.pos;
+    inp[r] = q.pos < q.n_prompt && !q.prompt.empty() ? q.prompt[q.pos] : q.next_input;
+    frc[r] = forced ? forced[s] : -1;
+    if (frc[r] < -1) frc[r] = -1;
+    inv_t[r] = q.inv_t;
+    sid[r] = q.seq_id;
+    kv_tokens += q.pos;
+    ++r;
+  }
+
+  // 4. run
+  if (!e->dry) {
+    HIP_TRY(hipSetDevice(c.device));
+    hipStream_t s = e->s_dec;
+    if (e->pt_dirty) {
+      HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
+      e->pt_dirty = false;
+    }
+    HIP_TRY(hipMemcpyAsync(e->meta_d, e->meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipEventRecord(e->ev_a, s));
+    int rc = enqueue_step(e, n);
+    if (rc) return rc;
+    HIP_TRY(hipEventRecord(e->ev_b, s));
+    HIP_TRY(hipMemcpyAsync(e->tok_h, e->tok_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(e->lp_h, e->lp_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipEventElapsedTime(&out->step_ms, e->ev_a, e->ev_b));
+    if (timed_stall) {
+      float t_total = 0.f;
+      HIP_TRY(hipEventElapsedTime(&t_total, e->ev_c, e->ev_a));
+      out->swap_stall_ms = t_total;
+    }
+  }
+
+  // 5. outputs and bookkeeping
+  r = 0;
+  for (int s = 0; s < c.max_batch; ++s) {
+    Seq &q = e->seqs[s];
+    if (!q.active) continue;
+    const int32_t tok = e->dry ? (frc[r] >= 0 ? frc[r] : -1) : e->tok_h[r];
+    const float lp = e->dry ? NAN : e->lp_h[r];
+    const bool emitted = q.pos >= q.n_prompt - 1;
+    if (emitted) { q.n_emitted++; q.next_input = tok; e->st.tokens_emitted++; }
+    const bool fin = emitted && q.n_emitted >= q.max_new;
+    if (out->slot) out->slot[r] = s;
+    if (out->seq_id) out->seq_id[r] = q.seq_id;
+    if (out->token) out->token[r] = tok;
+    if (out->logprob) out->logprob[r] = lp;
+    if (out->weight_version) out->weight_version[r] = e->version;
+    if (out->position) out->position[r] = q.pos;
+    if (out->emitted) out->emitted[r] = emitted;
+    if (out->finished) out->finished[r] = fin;
+    q.pos++;
+    ++r;
+  }
+  e->st.steps++;
+  e->st.slot_steps += n;
+  e->st.gpu_ms_total += out->step_ms;
+  const double kvb = 2.0 * c.n_layers * c.n_kv_heads * c.head_dim * 2.0;
+  e->st.algorithmic_bytes += (double)e->streamed_weight_bytes + (kv_tokens + n) * kvb;
+  return PL_OK;
+}
+
+int pl_get_stats(pl_engine *e, pl_stats *out) {
+  if (!e || !out) return fail(PL_E_INVAL, "NULL argument");
+  e->st.active_version = e->version;
+  e->st.kv_pages_free = (int64_t)e->free_pages.size();
+  *out = e->st;
+  return PL_OK;
+}
+
+int pl_debug_get_logits(pl_engine *e, float *out, int64_t out_elems) {
+  if (!e || !out) return fail(PL_E_INVAL, "NULL argument");
+  if (e->dry) return fail(PL_E_STATE, "bookkeeping-only engine computes no logits");
+  if (out_elems < (int64_t)e->last_n * e->cfg.vocab) return fail(PL_E_INVAL, "output buffer too small");
+  HIP_TRY(hipSetDevice(e->cfg.device));
+  HIP_TRY(hipMemcpy(out, e->logits, (size_t)e->last_n * e->cfg.vocab * 4, hipMemcpyDeviceToHost));
+  return PL_OK;
+}
+
+static int kv_xfer(pl_engine *e, int32_t slot, int32_t layer, float *k, float *v, const float *k_in,
+                   const float *v_in, int32_t n_ctx, bool write) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  if (e->dry) return fail(PL_E_STATE, "bookkeeping-only engine holds no KV");
+  const pl_model_cfg &c = e->cfg;
+  if (slot < 0 || slot >= c.max_batch || layer < 0 || layer >= c.n_layers) return fail(PL_E_INVAL, "slot or layer out of range");
+  Seq &q = e->seqs[slot];
+  if (!q.active) return fail(PL_E_STATE, "slot %d is idle", slot);
+  if (n_ctx < 0 || (int64_t)n_ctx > (int64_t)q.pages.size() * e->page_tokens) return fail(PL_E_INVAL, "n_ctx exceeds the slot's pages");
+  HIP_TRY(hipSetDevice(c.device));
+  HIP_TRY(hipStreamSynchronize(e->s_dec));
+  const int hd = c.head_dim, Hkv = c.n_kv_heads, ptok = e->page_tokens;
+  std::vector<uint16_t> img((size_t)e->page_stride);
+  for (int p0 = 0; p0 < n_ctx; p0 += ptok) {
+    bf16_t *dev = e->kv_pool + (int64_t)layer * e->layer_stride + (int64_t)q.pages[p0 / ptok] * e->page_stride;
+    HIP_TRY(hipMemcpy(img.data(), dev, img.size() * 2, hipMemcpyDeviceToHost));
+    const int cnt = std::min(ptok, n_ctx - p0);
+    for (int t = 0; t < cnt; ++t)
+      for (int g = 0; g < Hkv; ++g) {
+        uint16_t *kb = img.data() + (int64_t)g * 2 * ptok * hd, *vb = kb + (int64_t)ptok * hd;
+        for (int d = 0; d < hd; ++d) {
+          const int64_t ci = ((int64_t)(p0 + t) * Hkv + g) * hd + d;
+          if (write) {
+            kb[pl::k_elem_offset(t, d, hd)] = f32_to_bf16_bits(k_in[ci]);
+            vb[pl::v_elem_offset(t, d, hd)] = f32_to_bf16_bits(v_in[ci]);
+          } else {
+            k[ci] = bf16_bits_to_f32(kb[pl::k_elem_offset(t, d, hd)]);
+            v[ci] = bf16_bits_to_f32(vb[pl::v_elem_offset(t, d, hd)]);
+          }
+        }
+      }
+    if (write) HIP_TRY(hipMemcpy(dev, img.data(), img.size() * 2, hipMemcpyHostToDevice));
+  }
+  return PL_OK;
+}
+
+int pl_debug_read_kv(pl_engine *e, int32_t slot, int32_t layer, float *k_out, float *v_out, int32_t n_ctx) {
+  if (!k_out || !v_out) return fail(PL_E_INVAL, "NULL argument");
+  return kv_xfer(e, slot, layer, k_out, v_out, nullptr, nullptr, n_ctx, false);
+}
+
+int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_in, const float *v_in, int32_t n_ctx) {
+  if (!k_in || !v_in) return fail(PL_E_INVAL, "NULL argument");
+  return kv_xfer(e, slot, layer, nullptr, nullptr, k_in, v_in, n_ctx, true);
+}
+
+int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes) {
+  if (!e || !device_ptr || !nbytes) return fail(PL_E_INVAL, "NULL argument");
+  if (e->dry) return fail(PL_E_STATE, "bookkeeping-only engine holds no KV");
+  *device_ptr = e->kv_pool;
+  *nbytes = e->layer_stride * e->cfg.n_layers * 2;
+  return PL_OK;
+}
+
+// ---- kernel-level entry points ---------------------------------------------------------------------
+
+int64_t pl_attention_workspace_bytes(int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t hd, int32_t max_ctx) {
+  if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || hd < 1 || max_ctx < 1) return 0;
+  const int chunk = pl::attention_chunk_tokens(n_seq, n_kv_heads, max_ctx);
+  const int64_t max_chunks = (max_ctx + chunk - 1) / chunk;
+  return (int64_t)n_seq * n_q_heads * max_chunks * (hd + 2) * 4;
+}
+
+int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page_table, const int32_t *ctx_len,
+                        void *out, void *workspace, int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t hd,
+                        int32_t page_tokens, int32_t pages_per_seq, int32_t max_ctx, void *stream) {
+  if (!q || !kv_pages || !page_table || !ctx_len || !out || !workspace) return fail(PL_E_INVAL, "NULL argument");
+  if (n_seq < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || n_q_heads / n_kv_heads > 16) return fail(PL_E_INVAL, "bad head counts");
+  if (hd != 32 && hd != 64 && hd != 128) return fail(PL_E_INVAL, "head_dim must be 32, 64 or 128");
+  if (page_tokens < 32 || page_tokens % 32 || pages_per_seq < 1 || max_ctx < 1 || max_ctx > (int64_t)pages_per_seq * page_tokens)
+    return fail(PL_E_INVAL, "bad page geometry");
+  pl::AttnParams p{};
+  p.q = (const bf16_t *)q; p.kv = (const bf16_t *)kv_pages; p.page_table = page_table; p.ctx_len = ctx_len;
+  p.row_slot = nullptr; p.out = (bf16_t *)out;
+  p.n_seq = n_seq; p.Hq = n_q_heads; p.Hkv = n_kv_heads; p.hd = hd; p.page_tokens = page_tokens;
+  p.pages_per_seq = pages_per_seq;
+  p.chunk = pl::attention_chunk_tokens(n_seq, n_kv_heads, max_ctx);
+  p.max_chunks = (max_ctx + p.chunk - 1) / p.chunk;
+  const int64_t np = (int64_t)n_seq * n_q_heads * p.max_chunks;
+  p.part_o = (float *)workspace;
+  p.part_ml = p.part_o + np * hd;
+  if (pl::launch_attention(p, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
+  return PL_OK;
+}
+
+int pl_kv_pack_host(uint16_t *pages_host, const int32_t *page_ids, const float *k, const float *v, int32_t first_pos,
+                    int32_t n, int32_t n_kv_heads, int32_t hd, int32_t page_tokens) {
+  if (!pages_host || !page_ids || !k || !v) return fail(PL_E_INVAL, "NULL argument");
+  if (first_pos < 0 || n < 0 || n_kv_heads < 1 || page_tokens < 32 || page_tokens % 32 || (hd != 32 && hd != 64 && hd != 128))
+    return fail(PL_E_INVAL, "bad geometry");
+  const int64_t head_elems = (int64_t)2 * page_tokens * hd;
+  for (int i = 0; i < n; ++i) {
+    const int p = first_pos + i, t = p % page_tokens;
+    const int64_t page = page_ids[p / page_tokens];
+    for (int g = 0; g < n_kv_heads; ++g) {
+      uint16_t *kb = pages_host + (page * n_kv_heads + g) * head_elems, *vb = kb + (int64_t)page_tokens * hd;
+      for (int d = 0; d < hd; ++d) {
+        const int64_t ci = ((int64_t)i * n_kv_heads + g) * hd + d;
+        kb[pl::k_elem_offset(t, d, hd)] = f32_to_bf16_bits(k[ci]);
+        vb[pl::v_elem_offset(t, d, hd)] = f32_to_bf16_bits(v[ci]);
+      }
+    }
+  }
+  return PL_OK;
+}
+
+int pl_gemm_bf16(const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K, int32_t mode, int32_t splits,
+                 void *stream) {
+  if (!x || !w || !y) return fail(PL_E_INVAL, "NULL argument");
+  int rc = pl::launch_gemm((const bf16_t *)x, (const bf16_t *)w, y, M, N, K, mode, splits, (hipStream_t)stream);
+  if (rc == -1) return fail(PL_E_INVAL, "unsupported GEMM shape M=%d N=%d K=%d mode=%d splits=%d", M, N, K, mode, splits);
+  if (rc) return fail(PL_E_HIP, "GEMM launch failed");
+  return PL_OK;
+}
+
+int64_t pl_sample_workspace_bytes(int32_t n, int32_t vocab) {
+  if (n < 1 || vocab < 1) return 0;
+  return pl::sample_workspace_bytes(n, vocab);
+}
+
+int pl_sample(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq_id, const int32_t *position,
+              const float *inv_temperature, const int32_t *forced, uint64_t seed, int32_t *token, float *logprob,
+              void *workspace, void *stream) {
+  if (!logits || !seq_id || !position || !inv_temperature || !token || !logprob || !workspace) return fail(PL_E_INVAL, "NULL argument");
+  if (n < 1 || vocab < 4 || vocab % 4) return fail(PL_E_INVAL, "need n >= 1 and vocab a positive multiple of 4");
+  pl::SampleParams p{};
+  p.logits = logits; p.n = n; p.vocab = vocab; p.seq_id = seq_id; p.position = position; p.inv_t = inv_temperature;
+  p.forced = forced; p.seed = seed; p.token = token; p.logprob = logprob; p.workspace = workspace;
+  if (pl::launch_sample(p, (hipStream_t)stream)) return fail(PL_E_HIP, "sampler launch failed");
+  return PL_OK;
+}
+
+}  // extern "C"

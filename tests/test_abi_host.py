@@ -1,0 +1,184 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/pl.h declares, and its host
+logic (slot table, page accounting, version/flip rules, error codes) behaves as the Actor loop of
+Alg. 2 requires.  A bookkeeping-only engine (device = PL_DEVICE_NONE) computes no token."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_19128_amd as pl
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+M = synth.CONFIGS["tiny"]
+
+
+def _engine(**kw):
+    args = dict(max_batch=4, max_context=128, kv_pool_tokens=64 * 8, device=pl.PL_DEVICE_NONE, seed=1)
+    args.update(kw)
+    return pl.Engine.from_model(M, **args)
+
+
+def _loaded(**kw):
+    e = _engine(**kw)
+    e.load_weights(np.zeros(e.weight_nbytes() // 2, np.uint16))
+    return e
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "pl.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(pl_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(pl.EXPORTS)
+    L = pl.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_weight_layout_matches_documented_order_and_size():
+    e = _engine()
+    lay = e.weight_layout()
+    names = [n for n, _, _ in lay]
+    assert names[0] == "embed" and names[-2:] == ["gf", "lm_head"]
+    assert names[1:7] == ["l0.g1", "l0.w_qkv", "l0.w_o", "l0.g2", "l0.w_gu", "l0.w_d"]
+    off = 0
+    for _, o, (r, c) in lay:
+        assert o == off
+        off += r * c
+    assert off * 2 == e.weight_nbytes() == 2 * (M.streamed_params() + M.vocab * M.d_model)
+    # gate/up interleave and q|k|v row order are pure layout: packing then reading back is a permutation
+    W = synth.make_weights(M, 3)
+    blob = e.pack_weights(W, synth.f32_to_bf16_bits)
+    d = dict((n, (o, s)) for n, o, s in lay)
+    o, (r, c) = d["l1.w_gu"]
+    gu = synth.bf16_bits_to_f32(blob[o:o + r * c]).reshape(r, c)
+    assert np.array_equal(gu[64:96], synth.bf16_round(W["l1.wg"][32:64]))
+    assert np.array_equal(gu[96:128], synth.bf16_round(W["l1.wu"][32:64]))
+    o, (r, c) = d["l0.w_qkv"]
+    qkv = synth.bf16_bits_to_f32(blob[o:o + r * c]).reshape(r, c)
+    assert np.array_equal(qkv[M.q_dim:M.q_dim + M.kv_dim], synth.bf16_round(W["l0.wk"]))
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=7), dict(d_model=100), dict(vocab=100),
+                                 dict(n_kv_heads=0)])
+def test_create_rejects_unsupported_shapes(bad):
+    m = synth.ModelCfg(**{**M.__dict__, **bad})
+    with pytest.raises(pl.PlError) as ex:
+        pl.Engine.from_model(m, max_batch=2, max_context=64, kv_pool_tokens=128, device=pl.PL_DEVICE_NONE)
+    assert ex.value.code == pl.PL_E_INVAL
+
+
+def test_error_codes():
+    e = _engine()
+    with pytest.raises(pl.PlError) as ex:
+        e.decode_step()
+    assert ex.value.code == pl.PL_E_STATE                      # step before weights
+    with pytest.raises(pl.PlError) as ex:
+        e.swap_weights(np.zeros(e.weight_nbytes() // 2, np.uint16))
+    assert ex.value.code == pl.PL_E_STATE                      # swap before weights
+    with pytest.raises(pl.PlError) as ex:
+        e.load_weights(np.zeros(10, np.uint16))
+    assert ex.value.code == pl.PL_E_INVAL                      # wrong blob size
+    e = _loaded()
+    assert e.decode_step()["n"] == 0                           # no active slot: an empty step
+    for bad in (dict(temperature=0.0), dict(max_new=0), dict(prompt=[]), dict(prompt=[M.vocab])):
+        a = dict(seq_id=1, prompt=[1, 2], max_new=4, temperature=1.0)
+        a.update(bad)
+        with pytest.raises(pl.PlError) as ex:
+            e.add_sequence(**a)
+        assert ex.value.code == pl.PL_E_INVAL
+    with pytest.raises(pl.PlError) as ex:
+        e.add_sequence(1, [1] * 100, 30)
+    assert ex.value.code == pl.PL_E_CTX                        # 100 + 30 - 1 > 128
+    with pytest.raises(pl.PlError) as ex:
+        e.retire_sequence(2)
+    assert ex.value.code == pl.PL_E_STATE                      # idle slot
+    for i in range(4):
+        assert e.add_sequence(i, [1, 2, 3], 4) == i
+    with pytest.raises(pl.PlError) as ex:
+        e.add_sequence(9, [1], 1)
+    assert ex.value.code == pl.PL_E_NOSLOT
+    e.swap_weights(np.zeros(e.weight_nbytes() // 2, np.uint16), flags=pl.PL_SWAP_ASYNC)
+    with pytest.raises(pl.PlError) as ex:
+        e.swap_weights(np.zeros(e.weight_nbytes() // 2, np.uint16))
+    assert ex.value.code == pl.PL_E_BUSY                       # previous update not active yet
+    with pytest.raises(pl.PlError) as ex:
+        e.swap_weights(np.zeros(3, np.uint16))
+    assert ex.value.code == pl.PL_E_INVAL
+
+
+def test_kv_pool_exhaustion_leaves_engine_unchanged():
+    e = _loaded(kv_pool_tokens=64 * 3, max_context=128)
+    e.add_sequence(1, [1] * 60, 60)
+    e.add_sequence(2, [1] * 100, 5)                              # two pages
+    with pytest.raises(pl.PlError) as ex:
+        e.add_sequence(3, [1] * 10, 5)                           # pool is full
+    assert ex.value.code == pl.PL_E_NOKV and e.num_active() == 2
+    assert e.stats()["kv_pages_free"] == 0
+    for _ in range(64):
+        e.decode_step()
+    with pytest.raises(pl.PlError) as ex:                        # sequence 1 needs a second page now
+        e.decode_step()
+    assert ex.value.code == pl.PL_E_NOKV
+    st = e.stats()
+    assert st["steps"] == 64 and e.num_active() == 2
+    e.retire_sequence(1)                                         # sequence 2 (slot 1): frees two pages
+    assert e.stats()["kv_pages_free"] == 2
+    assert e.decode_step()["n"] == 1
+
+
+def test_life_cycle_refill_and_versions():
+    e = _loaded()
+    lens = {0: 3, 1: 5, 2: 2, 3: 4, 4: 3, 5: 2}
+    nxt, done = 0, {}
+    emitted = {}
+    for step in range(30):
+        while e.num_active() < 4 and nxt < len(lens):
+            e.add_sequence(nxt, [1, 2, 3], lens[nxt])
+            nxt += 1
+        if e.num_active() == 0:
+            break
+        if nxt < len(lens):
+            assert e.num_active() == 4                           # refilled to H before every step
+        if step == 4:
+            v = e.swap_weights(np.zeros(e.weight_nbytes() // 2, np.uint16), flags=pl.PL_SWAP_WAIT)
+            assert v == 1
+        r = e.decode_step()
+        assert len(set(r["weight_version"].tolist())) == 1       # one version per step
+        assert r["weight_version"][0] == (0 if step < 4 else 1)
+        for i in range(r["n"]):
+            sid = int(r["seq_id"][i])
+            assert bool(r["emitted"][i]) == (r["position"][i] >= 2)
+            emitted[sid] = emitted.get(sid, 0) + int(r["emitted"][i])
+            if r["finished"][i]:
+                done[sid] = int(r["position"][i]) + 1
+                e.retire_sequence(int(r["slot"][i]))
+    assert emitted == lens
+    assert done == {k: 3 + v - 1 for k, v in lens.items()}       # n_prompt + max_new - 1 cached positions
+    st = e.stats()
+    assert st["tokens_emitted"] == sum(lens.values()) and st["swaps"] == 1 and st["active_version"] == 1
+    assert st["kv_pages_free"] == st["kv_pages_total"]
+
+
+def test_forced_tokens_are_reported_and_async_swap_flips_at_a_step_boundary():
+    e = _loaded()
+    e.add_sequence(1, [5, 6], 3)
+    f = np.full(4, -1, np.int32)
+    f[0] = 77
+    assert e.decode_step(f)["token"][0] == 77
+    e.swap_weights(np.zeros(e.weight_nbytes() // 2, np.uint16), flags=pl.PL_SWAP_ASYNC)
+    assert e.swap_poll() == (True, 0)                            # staged, not active until a step runs
+    assert e.decode_step()["weight_version"][0] == 1
+    assert e.swap_poll() == (False, 1)
+
+
+def test_mid_flight_admission_hook():
+    e = _loaded()
+    s = e.debug_add_sequence_at(9, None, 16, 64, 1.0, context_len=70, n_emitted=55, last_token=3)
+    st = e.stats()
+    assert st["kv_pages_total"] - st["kv_pages_free"] == 2       # 70 positions: two 64-token pages
+    r = e.decode_step()
+    assert r["position"][0] == 70 and r["emitted"][0] == 1
+    with pytest.raises(pl.PlError):
+        e.debug_add_sequence_at(10, None, 16, 64, 1.0, context_len=5, n_emitted=0, last_token=3)  # prompt needed

@@ -1,0 +1,205 @@
+"""Kernel-level parity (GPU): the HIP kernels, called through the C ABI, against the CPU oracle on the
+same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_19128_amd as pl
+import synth
+from oracle import decoder, sampler
+
+from gpu_util import close, dev_bf16, to_np
+
+pytestmark = pytest.mark.gpu
+
+# spec tolerance for bf16 results
+ATOL, RTOL = 2e-2, 1e-2
+
+
+def _paged_inputs(rng, ctx, Hq, Hkv, hd, page_tokens, check_rows):
+    """Random page pool on the device; rows in `check_rows` get host-known K/V written into their pages."""
+    n = len(ctx)
+    pages_per_seq = (int(max(ctx)) + page_tokens - 1) // page_tokens
+    need = [(int(c) + page_tokens - 1) // page_tokens for c in ctx]
+    n_pages = sum(need) + 3
+    perm = rng.permutation(n_pages).astype(np.int32)
+    table = np.zeros((n, pages_per_seq), np.int32)
+    k = 0
+    for b in range(n):
+        table[b, :need[b]] = perm[k:k + need[b]]
+        k += need[b]
+    page_elems = Hkv * 2 * page_tokens * hd
+    g = torch.Generator(device="cuda").manual_seed(int(rng.integers(1 << 30)))
+    pool = torch.randn(n_pages * page_elems, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    known = {}
+    for b in check_rows:
+        c = int(ctx[b])
+        K = synth.bf16_round(rng.standard_normal((c, Hkv, hd)).astype(np.float32))
+        V = synth.bf16_round(rng.standard_normal((c, Hkv, hd)).astype(np.float32))
+        img = np.zeros(need[b] * page_elems, np.uint16)
+        pl.pl_kv_pack_host(img, np.arange(need[b], dtype=np.int32), K, V, 0, Hkv, hd, page_tokens)
+        dst = pool.view(torch.int16).view(n_pages, page_elems)
+        dst[torch.from_numpy(table[b, :need[b]].astype(np.int64)).cuda()] = torch.from_numpy(
+            img.view(np.int16).reshape(need[b], page_elems)).cuda()
+        known[b] = (K, V)
+    return pool, table, pages_per_seq, known
+
+
+def _run_attention(q_np, pool, table, ctx, Hq, Hkv, hd, page_tokens, pages_per_seq, max_ctx):
+    n = len(ctx)
+    q = dev_bf16(q_np)
+    out = torch.zeros(n, Hq, hd, device="cuda", dtype=torch.bfloat16)
+    ws = torch.empty(max(pl.pl_attention_workspace_bytes(n, Hq, Hkv, hd, max_ctx), 16), device="cuda", dtype=torch.uint8)
+    tb = torch.from_numpy(table).cuda()
+    cl = torch.from_numpy(np.asarray(ctx, np.int32)).cuda()
+    torch.cuda.synchronize()
+    pl.pl_attention_decode(q.data_ptr(), pool.data_ptr(), tb.data_ptr(), cl.data_ptr(), out.data_ptr(), ws.data_ptr(),
+                           n, Hq, Hkv, hd, page_tokens, pages_per_seq, max_ctx, 0)
+    torch.cuda.synchronize()
+    return to_np(out)
+
+
+@pytest.mark.parametrize("Hq,Hkv,hd,page_tokens", [(28, 4, 128, 64), (8, 2, 32, 64), (12, 2, 128, 32),
+                                                    (40, 8, 128, 128), (16, 1, 64, 64)])
+def test_attention_matches_oracle_on_ragged_contexts(Hq, Hkv, hd, page_tokens):
+    rng = np.random.default_rng(hd + Hq)
+    ctx = np.array([1, 31, 32, 33, 64, 127, 129, 700, 1500, 0, 5], np.int32)   # a zero-length row is skipped
+    pool, table, pps, known = _paged_inputs(rng, np.maximum(ctx, 1), Hq, Hkv, hd, page_tokens, range(len(ctx)))
+    q = synth.bf16_round(rng.standard_normal((len(ctx), Hq, hd)).astype(np.float32))
+    got = _run_attention(q, pool, table, ctx, Hq, Hkv, hd, page_tokens, pps, int(ctx.max()))
+    for b, c in enumerate(ctx):
+        if c == 0:
+            assert np.all(got[b] == 0)
+            continue
+        K, V = known[b]
+        ref = decoder.attend_one(q[b].astype(np.float64), K[:c].astype(np.float64), V[:c].astype(np.float64))
+        ok, err = close(got[b], ref, ATOL, RTOL)
+        assert ok, (b, c, err)
+
+
+def test_attention_closed_forms_on_device():
+    """q = 0 gives the mean of V; one cached token gives its value."""
+    rng = np.random.default_rng(5)
+    Hq, Hkv, hd, pt = 28, 4, 128, 64
+    ctx = np.array([300, 1], np.int32)
+    pool, table, pps, known = _paged_inputs(rng, ctx, Hq, Hkv, hd, pt, [0, 1])
+    q = synth.bf16_round(rng.standard_normal((2, Hq, hd)).astype(np.float32))
+    q[0] = 0
+    got = _run_attention(q, pool, table, ctx, Hq, Hkv, hd, pt, pps, 300)
+    for h in range(Hq):
+        assert close(got[0, h], known[0][1][:, h // 7].mean(0), ATOL, RTOL)[0]
+        assert close(got[1, h], known[1][1][0, h // 7], 1e-6, 4e-3)[0]
+
+
+def test_attention_full_microbench_shape_on_sampled_rows():
+    """The launch shape of the attention microbenchmark (batch 512, 28 q / 4 kv heads, head_dim 128,
+    log-normal contexts clipped to [128, 16384]); 12 sampled rows, shortest and longest included, are
+    checked against the oracle, the others only for being finite."""
+    rng = np.random.default_rng(1236)
+    Hq, Hkv, hd, pt = 28, 4, 128, 64
+    ctx = synth.attention_microbench_lengths(1236).astype(np.int32)
+    rows = sorted(set([int(ctx.argmin()), int(ctx.argmax())] + rng.choice(512, 10, replace=False).tolist()))
+    pool, table, pps, known = _paged_inputs(rng, ctx, Hq, Hkv, hd, pt, rows)
+    q = synth.bf16_round(rng.standard_normal((512, Hq, hd)).astype(np.float32))
+    got = _run_attention(q, pool, table, ctx, Hq, Hkv, hd, pt, pps, 16384)
+    assert np.isfinite(got).all()
+    for b in rows:
+        K, V = known[b]
+        ref = decoder.attend_one(q[b].astype(np.float64), K.astype(np.float64), V.astype(np.float64))
+        ok, err = close(got[b], ref, ATOL, RTOL)
+        assert ok, (b, int(ctx[b]), err)
+
+
+GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 256, 4), (3, 256, 1024, 2), (33, 320, 64, 1), (64, 2048, 1536, 3),
+               (130, 1536, 8960, 10), (256, 4608, 3584, 8), (200, 3584, 18944, 8), (256, 2560, 3584, 1),
+               (300, 640, 512, 2)]
+
+
+@pytest.mark.parametrize("M,N,K,splits", GEMM_SHAPES)
+def test_gemm_partials_sum_to_the_product(M, N, K, splits):
+    rng = np.random.default_rng(M * 7 + N)
+    x = synth.bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    w = synth.bf16_round((rng.standard_normal((N, K)) * 0.05).astype(np.float32))
+    xd, wd = dev_bf16(x), dev_bf16(w)
+    y = torch.full((splits, M, N), float("nan"), device="cuda", dtype=torch.float32)
+    pl.pl_gemm_bf16(xd.data_ptr(), wd.data_ptr(), y.data_ptr(), M, N, K, 0, splits, 0)
+    torch.cuda.synchronize()
+    got = to_np(y).astype(np.float64).sum(0)
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    ok, err = close(got, ref, 1e-4 * np.sqrt(K) * 0.05, 1e-4)      # fp32 accumulation of exact bf16 products
+    assert ok, err
+
+
+@pytest.mark.parametrize("M,F,K", [(4, 1024, 256), (64, 2240, 1536), (256, 1280, 3584), (129, 320, 128)])
+def test_gemm_swiglu_epilogue(M, F, K):
+    rng = np.random.default_rng(F + M)
+    x = synth.bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    wg = synth.bf16_round((rng.standard_normal((F, K)) * 0.05).astype(np.float32))
+    wu = synth.bf16_round((rng.standard_normal((F, K)) * 0.05).astype(np.float32))
+    inter = np.stack([wg.reshape(F // 32, 32, K), wu.reshape(F // 32, 32, K)], axis=1).reshape(2 * F, K)
+    y = torch.full((M, F), float("nan"), device="cuda", dtype=torch.bfloat16)
+    pl.pl_gemm_bf16(dev_bf16(x).data_ptr(), dev_bf16(inter).data_ptr(), y.data_ptr(), M, 2 * F, K, 1, 1, 0)
+    torch.cuda.synchronize()
+    x64 = x.astype(np.float64)
+    ref = decoder.silu(x64 @ wg.astype(np.float64).T) * (x64 @ wu.astype(np.float64).T)
+    ok, err = close(to_np(y), ref, 2e-3, RTOL)
+    assert ok, err
+
+
+def test_gemm_rejects_bad_shapes():
+    t = torch.zeros(64 * 64, device="cuda", dtype=torch.bfloat16)
+    for args in [(4, 64, 60, 0, 1), (0, 64, 64, 0, 1), (4, 64, 128, 0, 3), (4, 96, 64, 1, 1), (4, 64, 128, 1, 2),
+                 (4, 64, 64, 2, 1), (600, 64, 64, 0, 1)]:
+        with pytest.raises(pl.PlError) as ex:
+            pl.pl_gemm_bf16(t.data_ptr(), t.data_ptr(), t.data_ptr(), args[0], args[1], args[2], args[3], args[4], 0)
+        assert ex.value.code == pl.PL_E_INVAL
+
+
+def _gpu_sample(logits, seq_id, pos, temps, forced, seed):
+    n, V = logits.shape
+    lg = torch.from_numpy(logits).cuda()
+    sid = torch.from_numpy(np.asarray(seq_id, np.uint64).view(np.int64)).cuda()
+    ps = torch.from_numpy(np.asarray(pos, np.int32)).cuda()
+    it = torch.from_numpy((np.float32(1.0) / np.asarray(temps, np.float32)).astype(np.float32)).cuda()
+    fr = torch.from_numpy(np.asarray(forced, np.int32)).cuda()
+    tok = torch.zeros(n, device="cuda", dtype=torch.int32)
+    lp = torch.zeros(n, device="cuda", dtype=torch.float32)
+    ws = torch.empty(pl.pl_sample_workspace_bytes(n, V), device="cuda", dtype=torch.uint8)
+    pl.pl_sample(lg.data_ptr(), n, V, sid.data_ptr(), ps.data_ptr(), it.data_ptr(), fr.data_ptr(), seed,
+                 tok.data_ptr(), lp.data_ptr(), ws.data_ptr(), 0)
+    torch.cuda.synchronize()
+    return tok.cpu().numpy(), lp.cpu().numpy()
+
+
+@pytest.mark.parametrize("n,V", [(7, 4096), (4, 152064), (3, 151936), (5, 8)])
+def test_sampler_tokens_bit_exact_and_logprobs_close(n, V):
+    rng = np.random.default_rng(V + n)
+    logits = (rng.standard_normal((n, V)) * 2).astype(np.float32)
+    seq_id = rng.integers(0, 2**63, size=n, dtype=np.uint64) * np.uint64(2) + np.uint64(1)
+    pos = rng.integers(0, 16384, size=n).astype(np.int32)
+    temps = np.array([1.0, 0.7, 1.3, 1.0, 0.5, 2.0, 1.0][:n], np.float32)
+    forced = np.full(n, -1, np.int32)
+    forced[n - 1] = V // 3
+    seed = 0x1234567890ABCDEF
+    tok, lp = _gpu_sample(logits, seq_id, pos, temps, forced, seed)
+    for r in range(n):
+        t_ref, lp_ref = sampler.sample_row(logits[r], float(temps[r]), seed, int(seq_id[r]), int(pos[r]), int(forced[r]))
+        assert tok[r] == t_ref, (r, tok[r], t_ref)
+        assert abs(lp[r] - lp_ref) <= 1e-4 * max(1.0, abs(lp_ref))
+
+
+def test_sampler_ties_resolve_to_the_lowest_index_like_the_oracle():
+    """Constant logits: the winner is decided by the noise alone, and with 2^23 distinct uniforms over
+    152064 entries equal maxima do occur; both sides must pick the lowest index."""
+    n, V = 96, 152064
+    logits = np.zeros((n, V), np.float32)
+    seq_id = np.arange(n, dtype=np.uint64) + np.uint64(1 << 33)
+    pos = np.arange(n, dtype=np.int32) * 3
+    tok, lp = _gpu_sample(logits, seq_id, pos, np.ones(n, np.float32), np.full(n, -1, np.int32), 42)
+    ties = 0
+    for r in range(n):
+        g = sampler.gumbel_from_bits(__import__("oracle.philox", fromlist=["x"]).sampler_bits(42, int(seq_id[r]), int(pos[r]), V))
+        ties += int((g == g.max()).sum() > 1)
+        assert tok[r] == int(np.argmax(g))
+        assert abs(lp[r] + np.log(V)) < 1e-4
+    print("rows with tied maxima:", ties)
