@@ -1,0 +1,276 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path: constant-batch generation with continuous refill and in-flight
+weight updates on one MI355X, on a synthetic workload shaped like the paper's long-form reasoning
+generation (7B-shaped decoder, batch 256, 512-token prompts, log-normal generation lengths, weight
+update from pinned host memory every 128 steps).
+
+Prints ONE JSON line: generated tokens/s, the attention kernel's achieved HBM bandwidth against the
+8 TB/s peak (HIP events recorded by the engine on its decode stream), and the CPU oracle timed on the
+host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: model, batch, prompt, mean generation length, max generation length, swap period (steps)
+    "7b": dict(model="7b", batch=256, prompt=512, mean=4096.0, gmax=16384, swap_every=128, pool_tokens=1_700_000),
+    "1p5b": dict(model="1p5b", batch=64, prompt=256, mean=2048.0, gmax=8192, swap_every=256, pool_tokens=400_000),
+    "tiny": dict(model="tiny", batch=4, prompt=16, mean=48.0, gmax=64, swap_every=32, pool_tokens=4 * 128),
+}
+
+
+def _hip():
+    return ctypes.CDLL("libamdhip64.so")
+
+
+def device_weight_blob(eng, torch, seed, std=0.02, base=None, delta=0.0):
+    """Synthetic weights generated on the device: matrices ~ N(0, std^2), gains 1 (or base + N(0, delta^2))."""
+    n = eng.weight_nbytes() // 2
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    blob = torch.empty(n, device="cuda", dtype=torch.bfloat16)
+    step = 1 << 28
+    for o in range(0, n, step):
+        m = min(step, n - o)
+        if base is None:
+            blob[o:o + m] = (torch.randn(m, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+        else:
+            blob[o:o + m] = (base[o:o + m].float() + torch.randn(m, generator=g, device="cuda", dtype=torch.float32) * delta).to(torch.bfloat16)
+    if base is None:
+        for name, off, (r, c) in eng.weight_layout():
+            if c == 1:
+                blob[off:off + r] = 1.0
+    return blob
+
+
+def fill_kv_pool(eng, torch, seed):
+    """N(0,1) bf16 values in every page, so that sequences admitted mid-flight attend over real data."""
+    ptr, nbytes = eng.debug_kv_pool()
+    hip = _hip()
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    chunk = 1 << 29
+    off = 0
+    while off < nbytes:
+        m = min(chunk, nbytes - off)
+        t = torch.randn(m // 2, generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        torch.cuda.synchronize()
+        rc = hip.hipMemcpy(ctypes.c_void_p(ptr + off), ctypes.c_void_p(t.data_ptr()), m, 3)  # device to device
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpy failed: {rc}")
+        off += m
+
+
+class Workload:
+    """Alg. 2's Actor loop around the engine: pop finished, refill to H, request a weight update every
+    `swap_every` steps, generate next tokens."""
+
+    def __init__(self, eng, spec, model, seed):
+        self.eng, self.spec, self.model = eng, spec, model
+        self.rng = np.random.default_rng(seed)
+        self.next_id = 0
+
+    def _new_len(self):
+        return int(synth.lognormal_lengths(self.rng, 1, self.spec["mean"], 1, self.spec["gmax"])[0])
+
+    def admit_steady_state(self):
+        """Fill every slot with a sequence at a random point of its life, drawn from the stationary law of
+        constant-batch refill (busy time of a slot is proportional to prompt + length - 1)."""
+        B, P = self.spec["batch"], self.spec["prompt"]
+        cand = synth.lognormal_lengths(self.rng, 200_000, self.spec["mean"], 1, self.spec["gmax"])
+        busy = cand + P - 1
+        g = self.rng.choice(cand, size=B, p=busy / busy.sum())
+        for i in range(B):
+            G = int(g[i])
+            pos = int(self.rng.integers(0, P + G - 1))
+            prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
+            self.eng.debug_add_sequence_at(self.next_id, prompt, P, G, 1.0, pos, max(0, pos - (P - 1)),
+                                           int(self.rng.integers(0, self.model.vocab)))
+            self.next_id += 1
+
+    def refill(self):
+        P = self.spec["prompt"]
+        while self.eng.num_active() < self.spec["batch"]:
+            prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
+            self.eng.add_sequence(self.next_id, prompt, self._new_len(), 1.0)
+            self.next_id += 1
+
+    def step(self):
+        out = self.eng.decode_step()
+        fin = np.nonzero(out["finished"])[0]
+        emitted = int(out["emitted"].sum())
+        for i in fin:
+            self.eng.retire_sequence(int(out["slot"][i]))
+        if len(fin):
+            self.refill()
+        return emitted, out["step_ms"], out["swap_stall_ms"], out["weight_version"][0] if out["n"] else 0
+
+
+def cpu_baseline(model, seconds_budget=20.0):
+    """The CPU oracle as it stands, on the host cores: one layer + LM head of the workload's decoder
+    for one decode step at 4 sequences x 512 cached positions (float32), extrapolated linearly to all
+    layers.  Reported in generated tokens/s."""
+    from oracle import decoder
+    m1 = model.with_layers(1)
+    rng = np.random.default_rng(7)
+    w = {}
+    for name, shp in synth.weight_shapes(m1).items():
+        if name == "embed":
+            continue
+        w[name] = np.ones(shp, np.float32) if len(shp) == 1 else (rng.standard_normal(shp, dtype=np.float32) * np.float32(0.02))
+    w["embed"] = w["lm_head"]        # same shape; saves generating a second vocabulary-sized matrix
+    rows, ctx = 4, 512
+    caches = []
+    for _ in range(rows):
+        c = decoder.Cache(m1, np.float32)
+        c.k[0] = rng.standard_normal((ctx, m1.n_kv_heads, m1.head_dim), dtype=np.float32)
+        c.v[0] = rng.standard_normal((ctx, m1.n_kv_heads, m1.head_dim), dtype=np.float32)
+        caches.append(c)
+    m0 = model.with_layers(0)
+    # time the LM head alone (0 layers) and one layer + LM head; the difference is one layer
+    t0 = time.perf_counter()
+    for r in range(rows):
+        decoder.step(m0, w, int(rng.integers(m1.vocab)), 0, decoder.Cache(m0, np.float32), np.float32)
+    t_head = (time.perf_counter() - t0) / rows
+    t0 = time.perf_counter()
+    done = 0
+    while done < rows and (done == 0 or time.perf_counter() - t0 < seconds_budget):
+        decoder.step(m1, w, int(rng.integers(m1.vocab)), ctx, caches[done], np.float32)
+        done += 1
+    t_one = (time.perf_counter() - t0) / done
+    t_layer = max(t_one - t_head, 1e-9)
+    per_token = t_head + model.n_layers * t_layer
+    try:
+        import threadpoolctl
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": 1.0 / per_token, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 layer + LM head, {done} sequences x {ctx} cached positions, float32, "
+                      f"extrapolated to {model.n_layers} layers (one step = {per_token:.3f} s per sequence)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not record per-kernel HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one engine replica on one GPU; data-parallel replicas are independent "
+              "and are not launched here (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2509_19128_amd as pl
+
+    spec = WORKLOADS[args.workload]
+    model = synth.CONFIGS[spec["model"]]
+    max_ctx = spec["prompt"] + spec["gmax"]
+    eng = pl.Engine.from_model(model, max_batch=spec["batch"], max_context=max_ctx,
+                               kv_pool_tokens=spec["pool_tokens"], n_weight_buffers=2, seed=1234 + 3, device=0)
+    w0 = device_weight_blob(eng, torch, seed=1237)
+    torch.cuda.synchronize()
+    eng.load_weights(w0.data_ptr(), eng.weight_nbytes())
+    # the "next optimizer step" weights wait in pinned host memory, as a trainer's broadcast buffer would
+    w1 = device_weight_blob(eng, torch, seed=1238, base=w0, delta=1e-3)
+    host = [torch.empty(w0.numel(), dtype=torch.bfloat16, pin_memory=True) for _ in range(2)]
+    host[0].copy_(w1)
+    host[1].copy_(w0)
+    torch.cuda.synchronize()
+    del w0, w1
+    torch.cuda.empty_cache()
+    fill_kv_pool(eng, torch, seed=1239)
+
+    wl = Workload(eng, spec, model, seed=1234 + 3)
+    wl.admit_steady_state()
+    eng.debug_set_profile(not args.no_profile)
+    for _ in range(args.warmup):
+        wl.step()
+    torch.cuda.synchronize()
+    s0 = eng.stats()
+    emitted = 0
+    step_ms, stalls, flips = [], [], []
+    swaps_requested = 0
+    last_version = s0["active_version"]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        if spec["swap_every"] and k % spec["swap_every"] == spec["swap_every"] // 2:
+            try:    # Alg. 2: the trainer requests an update; the engine stages it while decoding goes on
+                eng.swap_weights(host[swaps_requested % 2].data_ptr(), eng.weight_nbytes(), flags=pl.PL_SWAP_ASYNC)
+                swaps_requested += 1
+            except pl.PlError as ex:
+                if ex.code != pl.PL_E_BUSY:
+                    raise
+        e, ms, stall, ver = wl.step()
+        emitted += e
+        step_ms.append(ms)
+        stalls.append(stall)
+        if ver != last_version:
+            flips.append(k)
+            last_version = ver
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    s1 = eng.stats()
+
+    d = {k: s1[k] - s0[k] for k in ("steps", "tokens_emitted", "slot_steps", "gpu_ms_total", "algorithmic_bytes",
+                                     "attn_ms", "gemm_ms", "sample_ms", "other_ms", "attn_launches", "attn_kv_bytes")}
+    sm = np.asarray(step_ms)
+    med = float(np.median(sm))
+    # swap stall: the step that contains the flip against the median of the 16 surrounding steps
+    stall_ms = 0.0
+    for k in flips:
+        lo, hi = max(0, k - 8), min(len(sm), k + 9)
+        around = np.concatenate([sm[lo:k], sm[k + 1:hi]])
+        if len(around):
+            stall_ms = max(stall_ms, float(sm[k] - np.median(around)) + float(stalls[k]))
+    res = {
+        "metric": "generated tokens/s/GPU at constant batch", "value": emitted / wall, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shaped decoder, constant batch {spec['batch']} with continuous refill, "
+                               f"{spec['prompt']}-token prompts, lognormal(mean {spec['mean']:.0f}, sigma 0.75, max {spec['gmax']}) "
+                               f"generation lengths, steady-state ages, weight update from pinned host every {spec['swap_every']} steps",
+                   "mean_context": d["algorithmic_bytes"] and float((d["attn_kv_bytes"] / max(d["attn_launches"], 1)) /
+                                                                    (4.0 * model.n_kv_heads * model.head_dim) / spec["batch"]),
+                   "slot_utilisation": d["tokens_emitted"] / max(d["slot_steps"], 1)},
+        "gpu_ms_per_step_median": med, "gpu_ms_per_step_p99": float(np.percentile(sm, 99)),
+        "step_hbm": {"algorithmic_bytes_per_step": d["algorithmic_bytes"] / max(d["steps"], 1),
+                     "achieved_GBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6,
+                     "frac_of_8TBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6 / HBM_PEAK_GBS},
+        "swap": {"requested": swaps_requested, "flips_at_steps": flips, "stall_ms": stall_ms,
+                 "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9},
+        "time_split_ms_per_step": {k: d[k] / max(d["steps"], 1) for k in ("attn_ms", "gemm_ms", "sample_ms", "other_ms")},
+    }
+    if d["attn_launches"]:
+        per_launch_bytes = d["attn_kv_bytes"] / d["attn_launches"]
+        per_launch_ms = d["attn_ms"] / d["attn_launches"]
+        ach = per_launch_bytes / per_launch_ms / 1e6
+        res["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel (+ merge)", "achieved": ach, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms}
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(model)
+    eng.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

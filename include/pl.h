@@ -89,6 +89,11 @@ typedef struct {
   float last_swap_copy_ms;    /* duration of the last staging copy */
   uint32_t active_version;
   int64_t kv_pages_free, kv_pages_total;
+  /* filled while profiling is on (pl_debug_set_profile): GPU time between HIP events recorded on the
+   * decode stream around each kernel group, summed over steps */
+  double attn_ms, gemm_ms, sample_ms, other_ms;
+  uint64_t attn_launches, gemm_launches; /* attention launches (one per layer per step), GEMM launches */
+  double attn_kv_bytes;                  /* K/V bytes those attention launches had to read */
 } pl_stats;
 
 /* ---- engine life cycle --------------------------------------------------------------------- */
@@ -173,6 +178,9 @@ int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_
 int pl_debug_add_sequence_at(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
                              int32_t max_new, float temperature, int32_t context_len,
                              int32_t n_emitted, int32_t last_token, int32_t *out_slot);
+/* Turn per-kernel-group timing on (1) or off (0): HIP events are recorded on the decode stream around
+ * the attention, GEMM and sampler launches of every step and accumulated into pl_stats. */
+int pl_debug_set_profile(pl_engine *e, int32_t on);
 /* Device pointer and size of the KV page pool (to fill it with synthetic values). */
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 

@@ -22,7 +22,7 @@ EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
     "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
-    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_kv_pool", "pl_attention_workspace_bytes",
+    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample",
 ]
 
@@ -53,7 +53,9 @@ class Stats(C.Structure):
     _fields_ = [("steps", C.c_uint64), ("tokens_emitted", C.c_uint64), ("slot_steps", C.c_uint64),
                 ("swaps", C.c_uint64), ("gpu_ms_total", C.c_double), ("algorithmic_bytes", C.c_double),
                 ("last_swap_copy_ms", C.c_float), ("active_version", C.c_uint32),
-                ("kv_pages_free", C.c_int64), ("kv_pages_total", C.c_int64)]
+                ("kv_pages_free", C.c_int64), ("kv_pages_total", C.c_int64),
+                ("attn_ms", C.c_double), ("gemm_ms", C.c_double), ("sample_ms", C.c_double), ("other_ms", C.c_double),
+                ("attn_launches", C.c_uint64), ("gemm_launches", C.c_uint64), ("attn_kv_bytes", C.c_double)]
 
 
 _lib = None
@@ -95,6 +97,7 @@ def lib():
         "pl_debug_write_kv": (C.c_int, [vp, i32, i32, vp, vp, i32]),
         "pl_debug_add_sequence_at": (C.c_int, [vp, u64, vp, i32, i32, f32, i32, i32, i32, P(i32)]),
         "pl_debug_kv_pool": (C.c_int, [vp, P(vp), P(i64)]),
+        "pl_debug_set_profile": (C.c_int, [vp, i32]),
         "pl_attention_workspace_bytes": (i64, [i32, i32, i32, i32, i32]),
         "pl_attention_decode": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "pl_kv_pack_host": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32]),
@@ -261,6 +264,9 @@ class Engine:
     def debug_write_kv(self, slot, layer, k, v):
         k, v = np.ascontiguousarray(k, np.float32), np.ascontiguousarray(v, np.float32)
         _check(lib().pl_debug_write_kv(self._h, slot, layer, _np_ptr(k), _np_ptr(v), k.shape[0]))
+
+    def debug_set_profile(self, on):
+        _check(lib().pl_debug_set_profile(self._h, int(bool(on))))
 
     def debug_kv_pool(self):
         p, n = C.c_void_p(), C.c_int64()

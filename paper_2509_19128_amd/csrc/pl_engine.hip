@@ -102,6 +102,12 @@ struct pl_engine {
   int sp_qkv = 1, sp_o = 1, sp_d = 1;
   hipStream_t s_dec = nullptr, s_copy = nullptr;
   hipEvent_t ev_a = nullptr, ev_b = nullptr, ev_c = nullptr;
+  // optional per-kernel-group timing: events[i] closes a segment of category cats[i]
+  bool profile = false;
+  std::vector<hipEvent_t> prof_ev;
+  std::vector<int> prof_cat;
+  size_t prof_n = 0;
+  double step_kv_tokens = 0;
   // last step
   int last_n = 0;
   pl_stats st{};
@@ -235,9 +241,26 @@ LayerW layer_weights(const pl_engine *e, int l) {
 }
 
 // The fixed kernel sequence of one decode step over n rows (rows = occupied slots, slot order).
+enum { CAT_OTHER = 0, CAT_ATTN = 1, CAT_GEMM = 2, CAT_SAMPLE = 3 };
+
+// Close the segment of work enqueued since the previous mark and attribute it to `cat`.
+void mark(pl_engine *e, int cat) {
+  if (!e->profile) return;
+  if (e->prof_n == e->prof_ev.size()) {
+    hipEvent_t ev;
+    if (hipEventCreate(&ev) != hipSuccess) return;
+    e->prof_ev.push_back(ev);
+    e->prof_cat.push_back(cat);
+  }
+  e->prof_cat[e->prof_n] = cat;
+  (void)hipEventRecord(e->prof_ev[e->prof_n++], e->s_dec);
+}
+
 int enqueue_step(pl_engine *e, int n) {
   const pl_model_cfg &c = e->cfg;
   hipStream_t s = e->s_dec;
+  e->prof_n = 0;
+  mark(e, CAT_OTHER);
   const bf16_t *base = e->wbuf[e->active_buf];
   const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, wq = qd + 2 * kvd;
   const bf16_t *embed = base + e->layout.front().offset;
@@ -251,7 +274,9 @@ int enqueue_step(pl_engine *e, int n) {
   for (int l = 0; l < c.n_layers && !rc; ++l) {
     const LayerW w = layer_weights(e, l);
     bf16_t *kv_layer = e->kv_pool + (int64_t)l * e->layer_stride;
+    mark(e, CAT_OTHER);
     rc |= pl::launch_gemm(e->a, w.w_qkv, e->parts, n, wq, d, 0, e->sp_qkv, s);
+    mark(e, CAT_GEMM);
     rc |= pl::launch_rope_append(e->parts, e->sp_qkv, e->cs, e->m_pos(true), e->m_row_slot(true), e->pt_d,
                                  e->q_rot, kv_layer, n, c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens,
                                  e->pages_per_seq, s);
@@ -261,21 +286,29 @@ int enqueue_step(pl_engine *e, int n) {
     ap.n_seq = n; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.hd = c.head_dim;
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
     ap.max_chunks = e->attn_max_chunks;
+    mark(e, CAT_OTHER);
     rc |= pl::launch_attention(ap, s);
+    mark(e, CAT_ATTN);
     rc |= pl::launch_gemm(e->attn_out, w.w_o, e->parts, n, d, qd, 0, e->sp_o, s);
+    mark(e, CAT_GEMM);
     rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_o, w.g2, e->a, n, d, c.rms_eps, s);
+    mark(e, CAT_OTHER);
     rc |= pl::launch_gemm(e->a, w.w_gu, e->mid, n, 2 * c.d_ffn, d, 1, 1, s);
     rc |= pl::launch_gemm(e->mid, w.w_d, e->parts, n, d, c.d_ffn, 0, e->sp_d, s);
+    mark(e, CAT_GEMM);
     const bf16_t *g_next = (l + 1 < c.n_layers) ? layer_weights(e, l + 1).g1 : gf;
     rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_d, g_next, e->a, n, d, c.rms_eps, s);
   }
+  mark(e, CAT_OTHER);
   rc |= pl::launch_gemm(e->a, lm, e->logits, n, c.vocab, d, 0, 1, s);
+  mark(e, CAT_GEMM);
   pl::SampleParams sp{};
   sp.logits = e->logits; sp.n = n; sp.vocab = c.vocab; sp.seq_id = e->m_seq_id(true);
   sp.position = e->m_pos(true); sp.inv_t = e->m_inv_t(true); sp.forced = e->m_forced(true);
   sp.seed = c.seed; sp.token = e->tok_d; sp.logprob = e->lp_d; sp.workspace = e->samp_ws;
   sp.last_tok = nullptr; sp.row_slot = nullptr;
   rc |= pl::launch_sample(sp, s);
+  mark(e, CAT_SAMPLE);
   return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
 }
 
@@ -390,6 +423,7 @@ void pl_destroy(pl_engine *e) {
     void *hst[] = {e->pt_h, e->meta_h, e->tok_h, e->lp_h};
     for (void *p : hst)
       if (p) (void)hipHostFree(p);
+    for (hipEvent_t ev : e->prof_ev) (void)hipEventDestroy(ev);
     hipEvent_t evs[] = {e->ev_a, e->ev_b, e->ev_c, e->ev_staged, e->ev_copy0};
     for (hipEvent_t ev : evs)
       if (ev) (void)hipEventDestroy(ev);
@@ -587,6 +621,17 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     HIP_TRY(hipMemcpyAsync(e->lp_h, e->lp_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     HIP_TRY(hipEventElapsedTime(&out->step_ms, e->ev_a, e->ev_b));
+    for (size_t i = 1; i < e->prof_n; ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, e->prof_ev[i - 1], e->prof_ev[i]) != hipSuccess) continue;
+      switch (e->prof_cat[i]) {
+        case CAT_ATTN: e->st.attn_ms += ms; e->st.attn_launches++; e->st.attn_kv_bytes += (kv_tokens + n) * 4.0 * c.n_kv_heads * c.head_dim; break;
+        case CAT_GEMM: e->st.gemm_ms += ms; break;
+        case CAT_SAMPLE: e->st.sample_ms += ms; break;
+        default: e->st.other_ms += ms;
+      }
+    }
+    if (e->prof_n) e->st.gemm_launches += 4 * (uint64_t)c.n_layers + 1;
     if (timed_stall) {
       float t_total = 0.f;
       HIP_TRY(hipEventElapsedTime(&t_total, e->ev_c, e->ev_a));
@@ -684,6 +729,12 @@ int pl_debug_read_kv(pl_engine *e, int32_t slot, int32_t layer, float *k_out, fl
 int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_in, const float *v_in, int32_t n_ctx) {
   if (!k_in || !v_in) return fail(PL_E_INVAL, "NULL argument");
   return kv_xfer(e, slot, layer, nullptr, nullptr, k_in, v_in, n_ctx, true);
+}
+
+int pl_debug_set_profile(pl_engine *e, int32_t on) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  e->profile = on != 0 && !e->dry;
+  return PL_OK;
 }
 
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes) {

@@ -238,7 +238,15 @@ def test_one_layer_slice_of_the_large_shapes(name, batch, ctx):
         if s % 8 == 0 or s >= ctx - 1:
             lg = eng.debug_get_logits(o["n"])
             for i, r in enumerate(recs):
-                ok, err = close(lg[i], orc.last_logits[r.slot], ATOL, RTOL)
+                ref = orc.last_logits[r.slot]
+                # The absolute tolerance is quoted for the tiny configuration, whose logits have rms 0.32
+                # (0.02 sqrt(256)); these shapes give rms 0.78 / 1.2, and the bf16 rounding error of a layer
+                # is proportional to the logit scale, so the absolute part is scaled by that ratio.  The
+                # error rms itself must stay below 1 % of the logit rms (a wrong index or head mapping
+                # gives errors of order 100 %).
+                scale = max(1.0, float(ref.std()) / 0.32)
+                ok, err = close(lg[i], ref, ATOL * scale, RTOL)
                 assert ok, (s, i, err)
-                assert abs(o["logprob"][i] - r.logprob) <= ATOL + RTOL * abs(r.logprob)
+                assert float((lg[i] - ref).std()) <= 1e-2 * float(ref.std()), (s, i)
+                assert abs(o["logprob"][i] - r.logprob) <= ATOL * scale + RTOL * abs(r.logprob)
     eng.close()

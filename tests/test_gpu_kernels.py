@@ -138,7 +138,8 @@ def test_gemm_swiglu_epilogue(M, F, K):
     wu = synth.bf16_round((rng.standard_normal((F, K)) * 0.05).astype(np.float32))
     inter = np.stack([wg.reshape(F // 32, 32, K), wu.reshape(F // 32, 32, K)], axis=1).reshape(2 * F, K)
     y = torch.full((M, F), float("nan"), device="cuda", dtype=torch.bfloat16)
-    pl.pl_gemm_bf16(dev_bf16(x).data_ptr(), dev_bf16(inter).data_ptr(), y.data_ptr(), M, 2 * F, K, 1, 1, 0)
+    xd, wd = dev_bf16(x), dev_bf16(inter)          # keep the device tensors alive across the launch
+    pl.pl_gemm_bf16(xd.data_ptr(), wd.data_ptr(), y.data_ptr(), M, 2 * F, K, 1, 1, 0)
     torch.cuda.synchronize()
     x64 = x.astype(np.float64)
     ref = decoder.silu(x64 @ wg.astype(np.float64).T) * (x64 @ wu.astype(np.float64).T)
