@@ -100,7 +100,7 @@ typedef struct {
 
 /* Create an engine: allocates weight buffer(s), the KV page pool and work buffers on cfg->device.
  * PL_E_INVAL if a shape is unsupported (head_dim not in {32, 64, 128}, n_q_heads not a multiple
- * of n_kv_heads or group > 16, d_model or d_ffn not a multiple of 64, ...). */
+ * of n_kv_heads or group > 16, d_model, d_ffn or n_q_heads*head_dim not a multiple of 256, ...). */
 int pl_create(const pl_model_cfg *cfg, pl_engine **out);
 void pl_destroy(pl_engine *e);
 const char *pl_last_error(void);
@@ -112,8 +112,12 @@ const char *pl_last_error(void);
  * "l<l>.g1" [d], "l<l>.w_qkv" [(Hq + 2 Hkv) hd, d] (rows: all q heads, all k heads, all v heads),
  * "l<l>.w_o" [d, Hq hd], "l<l>.g2" [d], "l<l>.w_gu" [2 F, d] (gate and up rows interleaved in
  * blocks of 32: rows [64 t, 64 t + 32) are gate rows 32 t .., rows [64 t + 32, 64 t + 64) the
- * matching up rows), "l<l>.w_d" [d, F]; then "gf" [d] and "lm_head" [vocab, d].  Every matrix is
- * row-major [out_features, in_features]: y = x W^T. */
+ * matching up rows), "l<l>.w_d" [d, F]; then "gf" [d] and "lm_head" [vocab, d].  Every matrix W is
+ * [out_features, in_features] (y = x W^T).  "embed" is row-major.  All other matrices are stored in
+ * MFMA operand order, so that a wavefront streams its rows with contiguous 1 KiB loads and all
+ * workgroups together read W plane by plane: in blocks of 32 rows x 64 columns, block (r / 32, c / 64)
+ * at element offset ((c / 64) (rows / 32) + r / 32) 2048 (column-block major), and inside a block
+ * element (r, c) at ((c % 32) / 8) 512 + ((c % 64) / 32) 256 + (r % 32) 8 + c % 8. */
 int32_t pl_weight_count(const pl_engine *e);
 int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t *offset_elems,
                      int64_t shape[2]);
@@ -213,10 +217,12 @@ int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page
 int pl_kv_pack_host(uint16_t *pages_host, const int32_t *page_ids, const float *k, const float *v,
                     int32_t first_pos, int32_t n, int32_t n_kv_heads, int32_t hd, int32_t page_tokens);
 
-/* y = x W^T with bf16 inputs and fp32 accumulation.  x device bf16 [M, K]; w device bf16 [N, K];
- * K a multiple of 64, N a multiple of 32, 1 <= M <= 512.
- *   mode 0: y device fp32 [splits, M, N]; slice s holds the partial sum over K range s (their sum
- *           over s is the product); splits >= 1 must divide K / 64.
+/* y = x W^T with bf16 inputs and fp32 accumulation.  x device bf16 [M, K] row-major; w device bf16
+ * [N, K] in MFMA operand order (see pl_weight_layout); K a multiple of 256, N a multiple of 32,
+ * 1 <= M <= 512.
+ *   mode 0: y device fp32 [splits, M, N]; slice s holds the partial sum over columns
+ *           [256 s c, min(256 (s + 1) c, K)), c = ceil((K / 256) / splits); their sum over s is the
+ *           product.  1 <= splits <= K / 256 and no slice may be empty.
  *   mode 1: SwiGLU: w holds gate/up rows interleaved in blocks of 32 (see pl_weight_layout);
  *           y device bf16 [M, N / 2] = silu(gate) * up; splits must be 1. */
 int pl_gemm_bf16(const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K,

@@ -9,7 +9,7 @@ import numpy as np
 __all__ = [
     "PL_OK", "PL_E_INVAL", "PL_E_NOSLOT", "PL_E_NOKV", "PL_E_BUSY", "PL_E_STATE", "PL_E_CTX", "PL_E_HIP",
     "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_DEVICE_NONE", "PlError", "ModelCfg", "StepOut", "Stats",
-    "lib", "library_path", "Engine", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
+    "lib", "library_path", "Engine", "operand_order", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
     "pl_gemm_bf16", "pl_sample", "pl_sample_workspace_bytes", "EXPORTS",
 ]
 
@@ -117,6 +117,13 @@ def _check(rc):
         raise PlError(rc, lib().pl_last_error().decode())
 
 
+def operand_order(w):
+    """[N, K] matrix -> the flat MFMA-operand-ordered image the GEMM kernels stream (layout only)."""
+    n, k = w.shape
+    assert n % 32 == 0 and k % 64 == 0, (n, k)
+    return np.ascontiguousarray(w.reshape(n // 32, 32, k // 64, 2, 4, 8).transpose(2, 0, 4, 3, 1, 5)).reshape(-1)
+
+
 def _np_ptr(a):
     return a.ctypes.data_as(C.c_void_p)
 
@@ -172,7 +179,7 @@ class Engine:
     def pack_weights(self, tensors, to_bits):
         """Flat uint16 (bf16 bits) blob from per-tensor fp32 arrays named wq/wk/wv/wo/wg/wu/wd/g1/g2
         per layer plus embed/gf/lm_head; `to_bits` converts fp32 -> bf16 bit patterns.  Row
-        concatenation and the 32-row gate/up interleave are layout only."""
+        concatenation, the 32-row gate/up interleave and the operand ordering are layout only."""
         blob = np.empty(self.weight_nbytes() // 2, np.uint16)
         for name, off, (r, c) in self.weight_layout():
             if name.endswith("w_qkv"):
@@ -190,7 +197,8 @@ class Engine:
             else:
                 src = tensors[name]
             assert src.size == r * c, (name, src.shape, r, c)
-            blob[off:off + r * c] = to_bits(np.ascontiguousarray(src, np.float32)).reshape(-1)
+            bits = to_bits(np.ascontiguousarray(src, np.float32)).reshape(src.shape)
+            blob[off:off + r * c] = bits.reshape(-1) if (c == 1 or name == "embed") else operand_order(bits)
         return blob
 
     def load_weights(self, src, nbytes=None):

@@ -15,11 +15,14 @@ namespace {
 
 __device__ inline float shfl_xor(float v, int mask) { return __shfl_xor(v, mask, 64); }
 
-template <int HD>
+template <int HD, int NS>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   constexpr int NJ = HD / 32;   // QK MFMAs per 16-token tile
   constexpr int NV = HD / 16;   // PV MFMAs per 32-token run
-  const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  // Workgroup ids are dealt round-robin to the 8 XCDs.  (sequence, kv head) is the fastest-varying
+  // index and the chunk the slowest, so every plane of equal chunk index, whose early members are
+  // all busy and whose late ones are mostly empty, is spread evenly over the XCDs.
+  const int g = blockIdx.x % p.Hkv, b = blockIdx.x / p.Hkv, c = blockIdx.y;
   const int ctx = p.ctx_len[b];
   const int t0 = c * p.chunk;
   if (t0 >= ctx) return;
@@ -57,66 +60,76 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
     return p.kv + ((int64_t)page * p.Hkv + g) * page_elems + (int64_t)r * 32 * HD + l * 8;
   };
 
-  bf16x8 kf[2][NJ], vf[NV];
-  auto load_run = [&](int blk) {
-    const bf16_t *kb = run_base(blk);
-    const bf16_t *vb = kb + (int64_t)p.page_tokens * HD;
+  // NS register stages per wavefront: stage s holds the K and V fragments of run (it * NS + s) * 4 +
+  // wave.  As soon as a stage's K fragments have gone through the QK MFMAs they are reloaded for the
+  // run NS rounds later, likewise the V fragments after the PV MFMAs, so about NS runs (16 KiB each)
+  // per wavefront are always in flight.
+  bf16x8 kf[NS][2][NJ], vf[NS][NV];
+  auto load_k = [&](int st, const bf16_t *kb) {
 #pragma unroll
     for (int T = 0; T < 2; ++T)
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) kf[T][j] = *(const bf16x8 *)(kb + (T * NJ + j) * 512);
-#pragma unroll
-    for (int i = 0; i < NV; ++i) vf[i] = *(const bf16x8 *)(vb + i * 512);
+      for (int j = 0; j < NJ; ++j) kf[st][T][j] = *(const bf16x8 *)(kb + (T * NJ + j) * 512);
   };
-
-  int blk = wave;
-  if (blk < nblk) load_run(blk);
-  while (blk < nblk) {
-    // scores of the 32 tokens of this run: two 16-token tiles
-    f32x4 s4[2];
+  auto load_v = [&](int st, const bf16_t *kb) {
+    const bf16_t *vb = kb + (int64_t)p.page_tokens * HD;
 #pragma unroll
-    for (int T = 0; T < 2; ++T) {
-      s4[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < NV; ++i) vf[st][i] = *(const bf16x8 *)(vb + i * 512);
+  };
 #pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        s4[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[T][j], qf[j], s4[T], 0, 0, 0);
+  for (int st = 0; st < NS; ++st) {
+    const int b0 = wave + 4 * st;
+    if (b0 < nblk) { const bf16_t *kb = run_base(b0); load_k(st, kb); load_v(st, kb); }
+  }
+  for (int base = wave; base < nblk; base += 4 * NS) {
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {
+      const int blk = base + 4 * st;
+      if (blk < nblk) {
+        // scores of the 32 tokens of this run: two 16-token tiles
+        f32x4 s4[2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+          s4[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            s4[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[st][T][j], qf[j], s4[T], 0, 0, 0);
+        }
+        const int nxt = blk + 4 * NS;
+        const bf16_t *nb = nullptr;
+        if (nxt < nblk) { nb = run_base(nxt); load_k(st, nb); }
+        const int tbase = t0 + blk * 32 + qg * 8;
+        float s[8];
+        float mb = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float v = s4[e >> 2][e & 3] * scale;
+          v = (tbase + e < t1) ? v : -INFINITY;
+          s[e] = v;
+          mb = fmaxf(mb, v);
+        }
+        mb = fmaxf(mb, shfl_xor(mb, 16));
+        mb = fmaxf(mb, shfl_xor(mb, 32));
+        const float m_new = fmaxf(m, mb);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        float psum = 0.f;
+        bf16x8 pf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float pe = __builtin_amdgcn_exp2f(s[e] - m_new);
+          psum += pe;
+          pf[e] = (__bf16)pe;
+        }
+        lsum = lsum * alpha + psum;
+        m = m_new;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          o[i] *= alpha;
+          o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[st][i], pf, o[i], 0, 0, 0);
+        }
+        if (nb) load_v(st, nb);
+      }
     }
-    bf16x8 vcur[NV];
-#pragma unroll
-    for (int i = 0; i < NV; ++i) vcur[i] = vf[i];
-    const int tbase = t0 + blk * 32 + qg * 8;
-    const int nxt = blk + 4;
-    if (nxt < nblk) load_run(nxt);   // next run's loads are in flight during the soft-max
-
-    float s[8];
-    float mb = -INFINITY;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float v = s4[e >> 2][e & 3] * scale;
-      v = (tbase + e < t1) ? v : -INFINITY;
-      s[e] = v;
-      mb = fmaxf(mb, v);
-    }
-    mb = fmaxf(mb, shfl_xor(mb, 16));
-    mb = fmaxf(mb, shfl_xor(mb, 32));
-    const float m_new = fmaxf(m, mb);
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-    float psum = 0.f;
-    bf16x8 pf;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float pe = __builtin_amdgcn_exp2f(s[e] - m_new);
-      psum += pe;
-      pf[e] = (__bf16)pe;
-    }
-    lsum = lsum * alpha + psum;
-    m = m_new;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      o[i] *= alpha;
-      o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vcur[i], pf, o[i], 0, 0, 0);
-    }
-    blk = nxt;
   }
   lsum += shfl_xor(lsum, 16);
   lsum += shfl_xor(lsum, 32);
@@ -185,18 +198,18 @@ int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx) {
 
 int launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_seq <= 0) return 0;
-  dim3 grid(p.max_chunks, p.Hkv, p.n_seq), cgrid(p.Hq, p.n_seq);
+  dim3 grid(p.n_seq * p.Hkv, p.max_chunks), cgrid(p.Hq, p.n_seq);
   switch (p.hd) {
     case 128:
-      hipLaunchKernelGGL(attn_decode_kernel<128>, grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL((attn_decode_kernel<128, 2>), grid, dim3(256), 0, s, p);
       hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(128), 0, s, p);
       break;
     case 64:
-      hipLaunchKernelGGL(attn_decode_kernel<64>, grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL((attn_decode_kernel<64, 2>), grid, dim3(256), 0, s, p);
       hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p);
       break;
     case 32:
-      hipLaunchKernelGGL(attn_decode_kernel<32>, grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL((attn_decode_kernel<32, 2>), grid, dim3(256), 0, s, p);
       hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(32), 0, s, p);
       break;
     default:

@@ -39,20 +39,43 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const bf16_t *embed,
 }
 
 // h[row] += sum_s parts[s][row]; a[row] = rmsnorm(h[row]) * g.  Partials are added in slice order.
+// The row (d <= 8192) stays in registers between the two passes; all loads are 16 bytes wide.
 __global__ __launch_bounds__(256) void resid_rmsnorm_kernel(float *h, const float *parts, int splits,
                                                             const bf16_t *g, bf16_t *a, int n, int d, float eps) {
-  const int row = blockIdx.x;
+  constexpr int NV = 8;
+  const int row = blockIdx.x, d4 = d >> 2;
+  float4 *h4 = (float4 *)(h + (int64_t)row * d);
+  float4 v[NV];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = h[(int64_t)row * d + i];
-    for (int s = 0; s < splits; ++s) v += parts[((int64_t)s * n + row) * d + i];
-    h[(int64_t)row * d + i] = v;
-    ss += v * v;
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int idx = threadIdx.x + it * 256;
+    if (idx < d4) {
+      float4 x = h4[idx];
+      for (int s = 0; s < splits; ++s) {
+        const float4 p = ((const float4 *)(parts + ((int64_t)s * n + row) * d))[idx];
+        x.x += p.x; x.y += p.y; x.z += p.z; x.w += p.w;
+      }
+      h4[idx] = x;
+      v[it] = x;
+      ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    }
   }
   ss = block_sum_256(ss);
   const float r = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256)
-    a[(int64_t)row * d + i] = (__bf16)(h[(int64_t)row * d + i] * r * (float)g[i]);
+#pragma unroll
+  for (int it = 0; it < NV; ++it) {
+    const int idx = threadIdx.x + it * 256;
+    if (idx < d4) {
+      const bf16x4 gg = ((const bf16x4 *)g)[idx];
+      bf16x4 o;
+      o[0] = (__bf16)(v[it].x * r * (float)gg[0]);
+      o[1] = (__bf16)(v[it].y * r * (float)gg[1]);
+      o[2] = (__bf16)(v[it].z * r * (float)gg[2]);
+      o[3] = (__bf16)(v[it].w * r * (float)gg[3]);
+      ((bf16x4 *)(a + (int64_t)row * d))[idx] = o;
+    }
+  }
 }
 
 // cos/sin of pos * theta^(-2i/hd), evaluated in double so long positions lose nothing; also the
@@ -70,43 +93,40 @@ __global__ void rope_tables_kernel(const int32_t *pos, float *cs, int32_t *ctx_l
 }
 
 // qkv (fp32, split-K partials) -> rotated q (bf16), rotated k and v into the row's cache page.
-__global__ __launch_bounds__(256) void rope_append_kernel(const float *qkv, int splits, const float *cs,
-                                                          const int32_t *pos, const int32_t *row_slot,
-                                                          const int32_t *page_table, bf16_t *q_out,
-                                                          bf16_t *kv_layer, int n, int Hq, int Hkv, int hd,
-                                                          int page_tokens, int pages_per_seq) {
-  const int row = blockIdx.x;
+// One block per (row, head of q|k|v), one thread per rotated pair.
+__global__ void rope_append_kernel(const float *qkv, int splits, const float *cs, const int32_t *pos,
+                                   const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out,
+                                   bf16_t *kv_layer, int n, int Hq, int Hkv, int hd, int page_tokens,
+                                   int pages_per_seq) {
+  const int row = blockIdx.y, hh = blockIdx.x, i = threadIdx.x;
   const int half = hd / 2;
   const int width = (Hq + 2 * Hkv) * hd;
+  float x1 = 0.f, x2 = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    const float *src = qkv + ((int64_t)s * n + row) * width + hh * hd;
+    x1 += src[i];
+    x2 += src[half + i];
+  }
+  if (hh < Hq) {
+    const float c = cs[(int64_t)row * hd + i], sn = cs[(int64_t)row * hd + half + i];
+    bf16_t *q = q_out + ((int64_t)row * Hq + hh) * hd;
+    q[i] = (__bf16)(x1 * c - x2 * sn);
+    q[half + i] = (__bf16)(x2 * c + x1 * sn);
+    return;
+  }
   const int p = pos[row];
   const int page = page_table[(int64_t)row_slot[row] * pages_per_seq + p / page_tokens];
   const int t = p % page_tokens;
-  const float *c = cs + (int64_t)row * hd, *sn = c + half;
-  auto val = [&](int col) {
-    float v = 0.f;
-    for (int s = 0; s < splits; ++s) v += qkv[((int64_t)s * n + row) * width + col];
-    return v;
-  };
   const int64_t page_elems = (int64_t)2 * page_tokens * hd;
-  // rotated pairs of the q and k heads
-  for (int idx = threadIdx.x; idx < (Hq + Hkv) * half; idx += 256) {
-    const int hh = idx / half, i = idx % half;
-    const float x1 = val(hh * hd + i), x2 = val(hh * hd + half + i);
-    const float y1 = x1 * c[i] - x2 * sn[i], y2 = x2 * c[i] + x1 * sn[i];
-    if (hh < Hq) {
-      bf16_t *q = q_out + ((int64_t)row * Hq + hh) * hd;
-      q[i] = (__bf16)y1;
-      q[half + i] = (__bf16)y2;
-    } else {
-      bf16_t *kb = kv_layer + ((int64_t)page * Hkv + (hh - Hq)) * page_elems;
-      kb[k_elem_offset(t, i, hd)] = (__bf16)y1;
-      kb[k_elem_offset(t, half + i, hd)] = (__bf16)y2;
-    }
-  }
-  for (int idx = threadIdx.x; idx < Hkv * hd; idx += 256) {
-    const int g = idx / hd, dd = idx % hd;
-    bf16_t *vb = kv_layer + ((int64_t)page * Hkv + g) * page_elems + (int64_t)page_tokens * hd;
-    vb[v_elem_offset(t, dd, hd)] = (__bf16)val((Hq + Hkv) * hd + idx);
+  if (hh < Hq + Hkv) {
+    const float c = cs[(int64_t)row * hd + i], sn = cs[(int64_t)row * hd + half + i];
+    bf16_t *kb = kv_layer + ((int64_t)page * Hkv + (hh - Hq)) * page_elems;
+    kb[k_elem_offset(t, i, hd)] = (__bf16)(x1 * c - x2 * sn);
+    kb[k_elem_offset(t, half + i, hd)] = (__bf16)(x2 * c + x1 * sn);
+  } else {
+    bf16_t *vb = kv_layer + ((int64_t)page * Hkv + (hh - Hq - Hkv)) * page_elems + (int64_t)page_tokens * hd;
+    vb[v_elem_offset(t, i, hd)] = (__bf16)x1;
+    vb[v_elem_offset(t, half + i, hd)] = (__bf16)x2;
   }
 }
 
@@ -149,8 +169,8 @@ int launch_rope_append(const float *qkv, int splits, const float *cs, const int3
                        const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out, bf16_t *kv_layer,
                        int n, int Hq, int Hkv, int hd, int page_tokens, int pages_per_seq, hipStream_t s) {
   if (n <= 0) return 0;
-  hipLaunchKernelGGL(rope_append_kernel, dim3(n), dim3(256), 0, s, qkv, splits, cs, pos, row_slot, page_table,
-                     q_out, kv_layer, n, Hq, Hkv, hd, page_tokens, pages_per_seq);
+  hipLaunchKernelGGL(rope_append_kernel, dim3(Hq + 2 * Hkv, n), dim3(hd / 2), 0, s, qkv, splits, cs, pos, row_slot,
+                     page_table, q_out, kv_layer, n, Hq, Hkv, hd, page_tokens, pages_per_seq);
   return ok();
 }
 

@@ -159,8 +159,8 @@ int check_cfg(const pl_model_cfg &c) {
   if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128) return fail(PL_E_INVAL, "head_dim must be 32, 64 or 128");
   if (c.n_q_heads % c.n_kv_heads || c.n_q_heads / c.n_kv_heads > 16)
     return fail(PL_E_INVAL, "n_q_heads must be a multiple of n_kv_heads with at most 16 query heads per kv head");
-  if (c.d_model % 64 || c.d_ffn % 64 || (c.n_q_heads * c.head_dim) % 64)
-    return fail(PL_E_INVAL, "d_model, d_ffn and n_q_heads*head_dim must be multiples of 64");
+  if (c.d_model % 256 || c.d_ffn % 256 || (c.n_q_heads * c.head_dim) % 256 || c.d_model > 8192)
+    return fail(PL_E_INVAL, "d_model (<= 8192), d_ffn and n_q_heads*head_dim must be multiples of 256");
   if (c.vocab % 32) return fail(PL_E_INVAL, "vocab must be a multiple of 32");
   if (c.max_batch < 1 || c.max_batch > 512) return fail(PL_E_INVAL, "max_batch must be in [1, 512]");
   if (c.max_context < 1) return fail(PL_E_INVAL, "max_context must be positive");

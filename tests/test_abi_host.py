@@ -51,16 +51,22 @@ def test_weight_layout_matches_documented_order_and_size():
     W = synth.make_weights(M, 3)
     blob = e.pack_weights(W, synth.f32_to_bf16_bits)
     d = dict((n, (o, s)) for n, o, s in lay)
-    o, (r, c) = d["l1.w_gu"]
-    gu = synth.bf16_bits_to_f32(blob[o:o + r * c]).reshape(r, c)
+    def rows(name):      # undo the operand ordering with the element formula of include/pl.h
+        o, (r, c) = d[name]
+        flat = synth.bf16_bits_to_f32(blob[o:o + r * c])
+        rr, cc = np.meshgrid(np.arange(r), np.arange(c), indexing="ij")
+        idx = ((cc // 64) * (r // 32) + rr // 32) * 2048 + ((cc % 32) // 8) * 512 + ((cc % 64) // 32) * 256 + (rr % 32) * 8 + cc % 8
+        return flat[idx]
+    gu = rows("l1.w_gu")
     assert np.array_equal(gu[64:96], synth.bf16_round(W["l1.wg"][32:64]))
     assert np.array_equal(gu[96:128], synth.bf16_round(W["l1.wu"][32:64]))
-    o, (r, c) = d["l0.w_qkv"]
-    qkv = synth.bf16_bits_to_f32(blob[o:o + r * c]).reshape(r, c)
+    qkv = rows("l0.w_qkv")
     assert np.array_equal(qkv[M.q_dim:M.q_dim + M.kv_dim], synth.bf16_round(W["l0.wk"]))
+    o, (r, c) = d["embed"]
+    assert np.array_equal(synth.bf16_bits_to_f32(blob[o:o + r * c]).reshape(r, c), synth.bf16_round(W["embed"]))
 
 
-@pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=7), dict(d_model=100), dict(vocab=100),
+@pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=7), dict(d_model=320), dict(vocab=100),
                                  dict(n_kv_heads=0)])
 def test_create_rejects_unsupported_shapes(bad):
     m = synth.ModelCfg(**{**M.__dict__, **bad})

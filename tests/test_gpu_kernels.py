@@ -110,8 +110,8 @@ def test_attention_full_microbench_shape_on_sampled_rows():
         assert ok, (b, int(ctx[b]), err)
 
 
-GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 256, 4), (3, 256, 1024, 2), (33, 320, 64, 1), (64, 2048, 1536, 3),
-               (130, 1536, 8960, 10), (256, 4608, 3584, 8), (200, 3584, 18944, 8), (256, 2560, 3584, 1),
+GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 1024, 4), (3, 256, 1024, 2), (33, 320, 256, 1), (64, 2048, 1536, 3),
+               (130, 1536, 8960, 7), (256, 4608, 3584, 7), (200, 3584, 18944, 8), (256, 3584, 18944, 9), (256, 2560, 3584, 1),
                (300, 640, 512, 2)]
 
 
@@ -120,7 +120,7 @@ def test_gemm_partials_sum_to_the_product(M, N, K, splits):
     rng = np.random.default_rng(M * 7 + N)
     x = synth.bf16_round(rng.standard_normal((M, K)).astype(np.float32))
     w = synth.bf16_round((rng.standard_normal((N, K)) * 0.05).astype(np.float32))
-    xd, wd = dev_bf16(x), dev_bf16(w)
+    xd, wd = dev_bf16(x), dev_bf16(pl.operand_order(w))
     y = torch.full((splits, M, N), float("nan"), device="cuda", dtype=torch.float32)
     pl.pl_gemm_bf16(xd.data_ptr(), wd.data_ptr(), y.data_ptr(), M, N, K, 0, splits, 0)
     torch.cuda.synchronize()
@@ -130,7 +130,7 @@ def test_gemm_partials_sum_to_the_product(M, N, K, splits):
     assert ok, err
 
 
-@pytest.mark.parametrize("M,F,K", [(4, 1024, 256), (64, 2240, 1536), (256, 1280, 3584), (129, 320, 128)])
+@pytest.mark.parametrize("M,F,K", [(4, 1024, 256), (64, 2240, 1536), (256, 1280, 3584), (129, 320, 512)])
 def test_gemm_swiglu_epilogue(M, F, K):
     rng = np.random.default_rng(F + M)
     x = synth.bf16_round(rng.standard_normal((M, K)).astype(np.float32))
@@ -138,7 +138,7 @@ def test_gemm_swiglu_epilogue(M, F, K):
     wu = synth.bf16_round((rng.standard_normal((F, K)) * 0.05).astype(np.float32))
     inter = np.stack([wg.reshape(F // 32, 32, K), wu.reshape(F // 32, 32, K)], axis=1).reshape(2 * F, K)
     y = torch.full((M, F), float("nan"), device="cuda", dtype=torch.bfloat16)
-    xd, wd = dev_bf16(x), dev_bf16(inter)          # keep the device tensors alive across the launch
+    xd, wd = dev_bf16(x), dev_bf16(pl.operand_order(inter))          # keep the device tensors alive across the launch
     pl.pl_gemm_bf16(xd.data_ptr(), wd.data_ptr(), y.data_ptr(), M, 2 * F, K, 1, 1, 0)
     torch.cuda.synchronize()
     x64 = x.astype(np.float64)
@@ -148,9 +148,9 @@ def test_gemm_swiglu_epilogue(M, F, K):
 
 
 def test_gemm_rejects_bad_shapes():
-    t = torch.zeros(64 * 64, device="cuda", dtype=torch.bfloat16)
-    for args in [(4, 64, 60, 0, 1), (0, 64, 64, 0, 1), (4, 64, 128, 0, 3), (4, 96, 64, 1, 1), (4, 64, 128, 1, 2),
-                 (4, 64, 64, 2, 1), (600, 64, 64, 0, 1)]:
+    t = torch.zeros(600 * 512, device="cuda", dtype=torch.bfloat16)
+    for args in [(4, 64, 192, 0, 1), (0, 64, 256, 0, 1), (4, 64, 512, 0, 3), (4, 96, 256, 1, 1), (4, 64, 512, 1, 2),
+                 (4, 64, 256, 2, 1), (600, 64, 256, 0, 1), (4, 48, 256, 0, 1)]:
         with pytest.raises(pl.PlError) as ex:
             pl.pl_gemm_bf16(t.data_ptr(), t.data_ptr(), t.data_ptr(), args[0], args[1], args[2], args[3], args[4], 0)
         assert ex.value.code == pl.PL_E_INVAL
