@@ -56,7 +56,7 @@ typedef struct {
   int32_t max_batch;      /* H of Alg. 2: number of slots */
   int32_t max_context;    /* cap on prompt + generated positions of one sequence */
   int64_t kv_pool_tokens; /* capacity of the paged KV pool, in token positions (all layers) */
-  int32_t kv_page_tokens; /* tokens per page: multiple of 32; 0 selects 64 */
+  int32_t kv_page_tokens; /* tokens per page: multiple of 32; 0 selects 128 */
   int32_t n_weight_buffers; /* 2: in-flight updates are staged into the inactive buffer; 1: updates
                                overwrite the only buffer and always block */
   uint64_t seed;          /* sampler key */

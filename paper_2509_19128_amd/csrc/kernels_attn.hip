@@ -19,13 +19,15 @@ template <int HD, int NS>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   constexpr int NJ = HD / 32;   // QK MFMAs per 16-token tile
   constexpr int NV = HD / 16;   // PV MFMAs per 32-token run
-  // Workgroup ids are dealt round-robin to the 8 XCDs.  (sequence, kv head) is the fastest-varying
-  // index and the chunk the slowest, so every plane of equal chunk index, whose early members are
-  // all busy and whose late ones are mostly empty, is spread evenly over the XCDs.
-  const int g = blockIdx.x % p.Hkv, b = blockIdx.x / p.Hkv, c = blockIdx.y;
+  // Work items come from a compact list of (sequence, chunk) pairs built on the device for this
+  // step: every launched workgroup up to the list's length has work (full chunks first, the partial
+  // last chunks of the sequences at the end), so consecutive workgroup ids, which the hardware deals
+  // round-robin to the 8 XCDs, load all XCDs evenly whatever the mix of context lengths.
+  const int item = blockIdx.x / p.Hkv, g = blockIdx.x % p.Hkv;
+  if (item >= p.work[0]) return;
+  const int b = p.work[1 + 2 * item], c = p.work[2 + 2 * item];
   const int ctx = p.ctx_len[b];
   const int t0 = c * p.chunk;
-  if (t0 >= ctx) return;
   const int t1 = min(ctx, t0 + p.chunk);
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int head = l & 15, qg = l >> 4;
@@ -166,6 +168,40 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   }
 }
 
+// work[0] = number of items, then (sequence, chunk) pairs: all full chunks, then each sequence's
+// last (partial or full) chunk.  One workgroup; n_seq <= 1024.
+__global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_len, int32_t *work, int n_seq,
+                                                             int chunk) {
+  __shared__ int sc[1024];
+  const int b = threadIdx.x;
+  const int n = b < n_seq ? (ctx_len[b] + chunk - 1) / chunk : 0;
+  const int full = n > 0 ? n - 1 : 0;
+  // inclusive scan of the full-chunk counts
+  sc[b] = full;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int v = b >= o ? sc[b - o] : 0;
+    __syncthreads();
+    sc[b] += v;
+    __syncthreads();
+  }
+  const int total_full = sc[1023];
+  int at = sc[b] - full;
+  for (int c = 0; c < full; ++c) { work[1 + 2 * (at + c)] = b; work[2 + 2 * (at + c)] = c; }
+  __syncthreads();
+  // then the last chunks, compacted over sequences with n > 0
+  sc[b] = n > 0;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    int v = b >= o ? sc[b - o] : 0;
+    __syncthreads();
+    sc[b] += v;
+    __syncthreads();
+  }
+  if (n > 0) { const int i = total_full + sc[b] - 1; work[1 + 2 * i] = b; work[2 + 2 * i] = n - 1; }
+  if (b == 0) work[0] = total_full + sc[1023];
+}
+
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnParams p) {
   const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
@@ -196,9 +232,18 @@ int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx) {
   return chunk;
 }
 
+int64_t attention_worklist_ints(int n_seq, int max_chunks) { return 1 + 2 * (int64_t)n_seq * max_chunks; }
+
+int launch_attention_worklist(const int32_t *ctx_len, int32_t *work, int n_seq, int chunk, hipStream_t s) {
+  if (n_seq <= 0 || n_seq > 1024) return -1;
+  hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, s, ctx_len, work, n_seq, chunk);
+  return hipGetLastError() == hipSuccess ? 0 : -7;
+}
+
 int launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_seq <= 0) return 0;
-  dim3 grid(p.n_seq * p.Hkv, p.max_chunks), cgrid(p.Hq, p.n_seq);
+  // max_items bounds the list (the host knows the longest context of the step, or uses max_chunks)
+  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hq, p.n_seq);
   switch (p.hd) {
     case 128:
       hipLaunchKernelGGL((attn_decode_kernel<128, 2>), grid, dim3(256), 0, s, p);

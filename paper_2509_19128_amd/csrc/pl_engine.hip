@@ -93,7 +93,8 @@ struct pl_engine {
   // work buffers
   float *h = nullptr, *parts = nullptr, *logits = nullptr, *cs = nullptr, *attn_po = nullptr, *attn_pml = nullptr;
   bf16_t *a = nullptr, *q_rot = nullptr, *attn_out = nullptr, *mid = nullptr;
-  int32_t *ctx_len = nullptr, *tok_d = nullptr;
+  int32_t *ctx_len = nullptr, *tok_d = nullptr, *attn_work = nullptr;
+  int attn_items = 0;   // bound on this step's attention work items
   float *lp_d = nullptr;
   void *samp_ws = nullptr;
   int32_t *tok_h = nullptr;
@@ -221,6 +222,7 @@ int alloc_device(pl_engine *e) {
   const int64_t np = (int64_t)B * c.n_kv_heads * e->attn_max_chunks * e->G;
   if ((rc = dev_alloc(&e->attn_po, np * c.head_dim))) return rc;
   if ((rc = dev_alloc(&e->attn_pml, np * 2))) return rc;
+  if ((rc = dev_alloc(&e->attn_work, pl::attention_worklist_ints(B, e->attn_max_chunks)))) return rc;
   char *ws = nullptr;
   if ((rc = dev_alloc(&ws, pl::sample_workspace_bytes(B, c.vocab)))) return rc;
   e->samp_ws = ws;
@@ -268,6 +270,7 @@ int enqueue_step(pl_engine *e, int n) {
   const bf16_t *lm = base + e->layout.back().offset;
   int rc = 0;
   rc |= pl::launch_rope_tables(e->m_pos(true), e->cs, e->ctx_len, n, c.head_dim, c.rope_theta, s);
+  rc |= pl::launch_attention_worklist(e->ctx_len, e->attn_work, n, e->attn_chunk, s);
   const bf16_t *g_first = c.n_layers ? layer_weights(e, 0).g1 : gf;
   rc |= pl::launch_embed_rmsnorm(embed, g_first, e->m_input(true), nullptr, e->m_row_slot(true), e->h, e->a, n,
                                  d, c.vocab, c.rms_eps, s);
@@ -286,6 +289,7 @@ int enqueue_step(pl_engine *e, int n) {
     ap.n_seq = n; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.hd = c.head_dim;
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
     ap.max_chunks = e->attn_max_chunks;
+    ap.work = e->attn_work; ap.max_items = e->attn_items;
     mark(e, CAT_OTHER);
     rc |= pl::launch_attention(ap, s);
     mark(e, CAT_ATTN);
@@ -380,7 +384,7 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
   e->cfg = *cfg;
   e->dry = cfg->device == PL_DEVICE_NONE;
   e->G = cfg->n_q_heads / cfg->n_kv_heads;
-  e->page_tokens = cfg->kv_page_tokens ? cfg->kv_page_tokens : 64;
+  e->page_tokens = cfg->kv_page_tokens ? cfg->kv_page_tokens : 128;
   e->pages_per_seq = (cfg->max_context + e->page_tokens - 1) / e->page_tokens;
   e->n_pages = cfg->kv_pool_tokens / e->page_tokens;
   if (e->n_pages < 1 || e->n_pages > 0x7FFFFFFF) {
@@ -417,7 +421,7 @@ void pl_destroy(pl_engine *e) {
     if (e->s_copy) (void)hipStreamSynchronize(e->s_copy);
     void *dev[] = {e->wbuf[0], e->wbuf[1], e->kv_pool, e->pt_d, e->meta_d, e->h, e->a, e->parts, e->q_rot,
                    e->attn_out, e->mid, e->logits, e->cs, e->ctx_len, e->tok_d, e->lp_d, e->attn_po,
-                   e->attn_pml, e->samp_ws};
+                   e->attn_pml, e->samp_ws, e->attn_work};
     for (void *p : dev)
       if (p) (void)hipFree(p);
     void *hst[] = {e->pt_h, e->meta_h, e->tok_h, e->lp_h};
@@ -584,6 +588,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   uint64_t *sid = e->m_seq_id(false);
   int r = 0;
   double kv_tokens = 0;
+  int items = 0;
   for (int s = 0; s < c.max_batch; ++s) {
     Seq &q = e->seqs[s];
     if (!q.active) continue;
@@ -601,8 +606,11 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     inv_t[r] = q.inv_t;
     sid[r] = q.seq_id;
     kv_tokens += q.pos;
+    items += (q.pos + 1 + e->attn_chunk - 1) / e->attn_chunk;
     ++r;
   }
+
+  e->attn_items = items;
 
   // 4. run
   if (!e->dry) {
@@ -751,7 +759,7 @@ int64_t pl_attention_workspace_bytes(int32_t n_seq, int32_t n_q_heads, int32_t n
   if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || hd < 1 || max_ctx < 1) return 0;
   const int chunk = pl::attention_chunk_tokens(n_seq, n_kv_heads, max_ctx);
   const int64_t max_chunks = (max_ctx + chunk - 1) / chunk;
-  return (int64_t)n_seq * n_q_heads * max_chunks * (hd + 2) * 4;
+  return (int64_t)n_seq * n_q_heads * max_chunks * (hd + 2) * 4 + pl::attention_worklist_ints(n_seq, (int)max_chunks) * 4;
 }
 
 int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page_table, const int32_t *ctx_len,
@@ -772,6 +780,11 @@ int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page
   const int64_t np = (int64_t)n_seq * n_q_heads * p.max_chunks;
   p.part_o = (float *)workspace;
   p.part_ml = p.part_o + np * hd;
+  int32_t *work = (int32_t *)(p.part_ml + np * 2);
+  p.work = work;
+  p.max_items = n_seq * p.max_chunks;
+  if (n_seq > 1024) return fail(PL_E_INVAL, "at most 1024 sequences per launch");
+  if (pl::launch_attention_worklist(ctx_len, work, n_seq, p.chunk, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
   if (pl::launch_attention(p, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
   return PL_OK;
 }

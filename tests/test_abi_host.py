@@ -15,7 +15,7 @@ M = synth.CONFIGS["tiny"]
 
 
 def _engine(**kw):
-    args = dict(max_batch=4, max_context=128, kv_pool_tokens=64 * 8, device=pl.PL_DEVICE_NONE, seed=1)
+    args = dict(max_batch=4, max_context=128, kv_pool_tokens=64 * 8, kv_page_tokens=64, device=pl.PL_DEVICE_NONE, seed=1)
     args.update(kw)
     return pl.Engine.from_model(M, **args)
 

@@ -31,7 +31,7 @@ def weights():
 
 
 def _engine(max_batch=4, **kw):
-    args = dict(max_batch=max_batch, max_context=128, kv_pool_tokens=max_batch * 128, seed=SEED, device=0)
+    args = dict(max_batch=max_batch, max_context=128, kv_pool_tokens=max_batch * 128, kv_page_tokens=32, seed=SEED, device=0)
     args.update(kw)
     return pl.Engine.from_model(M, **args)
 
@@ -222,7 +222,7 @@ def test_one_layer_slice_of_the_large_shapes(name, batch, ctx):
     of rows, short contexts: the oracle runs in float32 here to bound its memory."""
     m = synth.CONFIGS[name].with_layers(1)
     w = synth.make_weights(m, seed=4321)
-    eng = pl.Engine.from_model(m, max_batch=batch, max_context=64, kv_pool_tokens=batch * 64, seed=SEED, device=0)
+    eng = pl.Engine.from_model(m, max_batch=batch, max_context=64, kv_pool_tokens=batch * 128, seed=SEED, device=0)
     eng.load_weights(eng.pack_weights(w, synth.f32_to_bf16_bits))
     wr = {k: synth.bf16_round(v) for k, v in w.items()}
     orc = OracleEngine(m, wr, max_batch=batch, seed=SEED, dtype=np.float32)
