@@ -172,6 +172,8 @@ def main():
     ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not record per-kernel HIP events")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="finish with three plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one engine replica on one GPU; data-parallel replicas are independent "
@@ -266,6 +268,12 @@ def main():
         res["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel (+ merge)", "achieved": ach, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
                            "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms}
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(model)
     eng.close()

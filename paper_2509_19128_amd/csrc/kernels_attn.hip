@@ -10,6 +10,13 @@
 // chunks of one sequence are merged by a second kernel in a fixed order.
 #include "pl_common.h"
 
+#ifndef PL_ATTN_NS
+#define PL_ATTN_NS 2   // register stages of K/V runs per wavefront
+#endif
+#ifndef PL_ATTN_CHUNK
+#define PL_ATTN_CHUNK 2048   // largest number of tokens one workgroup handles
+#endif
+
 namespace pl {
 namespace {
 
@@ -189,16 +196,22 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
   int at = sc[b] - full;
   for (int c = 0; c < full; ++c) { work[1 + 2 * (at + c)] = b; work[2 + 2 * (at + c)] = c; }
   __syncthreads();
-  // then the last chunks, compacted over sequences with n > 0
+  // then the last chunks, longest first, so that the workgroups still running when the grid drains
+  // are the short ones
+  __shared__ int tail[1024];
+  const int rem = n > 0 ? ctx_len[b] - (n - 1) * chunk : 0;
+  tail[b] = rem;
   sc[b] = n > 0;
   __syncthreads();
+  int rank = 0;
+  for (int o = 0; o < n_seq; ++o) rank += (tail[o] > rem) || (tail[o] == rem && o < b && tail[o] > 0);
+  if (n > 0) { const int i = total_full + rank; work[1 + 2 * i] = b; work[2 + 2 * i] = n - 1; }
   for (int o = 1; o < 1024; o <<= 1) {
     int v = b >= o ? sc[b - o] : 0;
     __syncthreads();
     sc[b] += v;
     __syncthreads();
   }
-  if (n > 0) { const int i = total_full + sc[b] - 1; work[1 + 2 * i] = b; work[2 + 2 * i] = n - 1; }
   if (b == 0) work[0] = total_full + sc[1023];
 }
 
@@ -227,7 +240,7 @@ int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx) {
   // Tokens per workgroup: large enough that the merge is a small fraction of the bytes, small
   // enough that a few hundred compute units all get work.  A function of the launch shape only,
   // never of the contexts, so a sequence's result does not depend on its neighbours' lengths.
-  int chunk = 1024;
+  int chunk = PL_ATTN_CHUNK;
   while (chunk > 128 && (int64_t)n_seq * Hkv * ((max_ctx + chunk - 1) / chunk) < 2048) chunk >>= 1;
   return chunk;
 }
@@ -246,15 +259,15 @@ int launch_attention(const AttnParams &p, hipStream_t s) {
   dim3 grid(p.max_items * p.Hkv), cgrid(p.Hq, p.n_seq);
   switch (p.hd) {
     case 128:
-      hipLaunchKernelGGL((attn_decode_kernel<128, 2>), grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL((attn_decode_kernel<128, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
       hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(128), 0, s, p);
       break;
     case 64:
-      hipLaunchKernelGGL((attn_decode_kernel<64, 2>), grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL((attn_decode_kernel<64, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
       hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p);
       break;
     case 32:
-      hipLaunchKernelGGL((attn_decode_kernel<32, 2>), grid, dim3(256), 0, s, p);
+      hipLaunchKernelGGL((attn_decode_kernel<32, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
       hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(32), 0, s, p);
       break;
     default:
