@@ -120,6 +120,23 @@ class Workload:
         return emitted, out["step_ms"], out["swap_stall_ms"], out["weight_version"][0] if out["n"] else 0
 
 
+def stream_ceiling(torch, pl):
+    """Read bandwidth HBM delivers to a kernel that only reads (GB/s), timed with events on torch's
+    current stream, where the probe is launched."""
+    buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    buf.random_(0, 255)
+    best = 0.0
+    s = torch.cuda.current_stream()
+    for _ in range(5):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(s)
+        n = pl.pl_debug_stream_read(buf.data_ptr(), buf.numel(), s.cuda_stream)
+        b.record(s)
+        torch.cuda.synchronize()
+        best = max(best, n / (a.elapsed_time(b) * 1e-3) / 1e9)
+    return best
+
+
 def cpu_baseline(model, seconds_budget=20.0):
     """The CPU oracle as it stands, on the host cores: one layer + LM head of the workload's decoder
     for one decode step at 4 sequences x 512 cached positions (float32), extrapolated linearly to all
@@ -261,12 +278,16 @@ def main():
                  "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9},
         "time_split_ms_per_step": {k: d[k] / max(d["steps"], 1) for k in ("attn_ms", "gemm_ms", "sample_ms", "other_ms")},
     }
+    res["hbm_read_stream_ceiling_GBs"] = stream_ceiling(torch, pl)
     if d["attn_launches"]:
         per_launch_bytes = d["attn_kv_bytes"] / d["attn_launches"]
         per_launch_ms = d["attn_ms"] / d["attn_launches"]
         ach = per_launch_bytes / per_launch_ms / 1e6
         res["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel (+ merge)", "achieved": ach, "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                           "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                           # rocprofv3 FETCH_SIZE (x2.0, calibrated on plain copies) + WRITE_SIZE per launch came to
+                           # 1.01 x the algorithmic bytes on this workload (profiles/decode_step_7b_b256.md)
+                           "traffic": 1.01 * per_launch_bytes if args.workload == "7b" else None,
                            "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms}
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")

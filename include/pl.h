@@ -188,6 +188,11 @@ int pl_debug_set_profile(pl_engine *e, int32_t on);
 /* Device pointer and size of the KV page pool (to fill it with synthetic values). */
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 
+/* Launch a kernel that only reads the device buffer (contiguous 16-byte loads, 8 in flight per lane)
+ * on `stream`; returns the number of bytes it reads (a multiple of 256 MiB, <= nbytes) or a negative
+ * pl_status.  Timed by the caller, it gives the read bandwidth HBM delivers on this board. */
+int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, void *stream);
+
 /* ---- kernel-level entry points (device pointers; `stream` is a hipStream_t or NULL) ----------- */
 
 /* Ragged grouped-query decode attention over a paged bf16 cache: for every sequence b < n_seq and

@@ -10,7 +10,7 @@ __all__ = [
     "PL_OK", "PL_E_INVAL", "PL_E_NOSLOT", "PL_E_NOKV", "PL_E_BUSY", "PL_E_STATE", "PL_E_CTX", "PL_E_HIP",
     "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_DEVICE_NONE", "PlError", "ModelCfg", "StepOut", "Stats",
     "lib", "library_path", "Engine", "operand_order", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
-    "pl_gemm_bf16", "pl_sample", "pl_sample_workspace_bytes", "EXPORTS",
+    "pl_gemm_bf16", "pl_sample", "pl_sample_workspace_bytes", "pl_debug_stream_read", "EXPORTS",
 ]
 
 PL_OK, PL_E_INVAL, PL_E_NOSLOT, PL_E_NOKV, PL_E_BUSY, PL_E_STATE, PL_E_CTX, PL_E_HIP, PL_E_NOMEM = 0, -1, -2, -3, -4, -5, -6, -7, -8
@@ -22,7 +22,7 @@ EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
     "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
-    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_attention_workspace_bytes",
+    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample",
 ]
 
@@ -98,6 +98,7 @@ def lib():
         "pl_debug_add_sequence_at": (C.c_int, [vp, u64, vp, i32, i32, f32, i32, i32, i32, P(i32)]),
         "pl_debug_kv_pool": (C.c_int, [vp, P(vp), P(i64)]),
         "pl_debug_set_profile": (C.c_int, [vp, i32]),
+        "pl_debug_stream_read": (i64, [vp, i64, vp]),
         "pl_attention_workspace_bytes": (i64, [i32, i32, i32, i32, i32]),
         "pl_attention_decode": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "pl_kv_pack_host": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32]),
@@ -201,6 +202,36 @@ class Engine:
             blob[off:off + r * c] = bits.reshape(-1) if (c == 1 or name == "embed") else operand_order(bits)
         return blob
 
+    def unpack_weights(self, blob, from_bits, names=None):
+        """Inverse of pack_weights: per-tensor fp32 arrays (wq/wk/wv/wo/wg/wu/wd/g1/g2, embed, gf, lm_head)
+        from a flat uint16 blob.  `names`: restrict to these blob tensors (e.g. one layer at a time)."""
+        cfg, out = self.cfg, {}
+        qd, kvd = cfg.n_q_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+        for name, off, (r, c) in self.weight_layout():
+            if names is not None and name not in names:
+                continue
+            bits = np.asarray(blob[off:off + r * c])
+            if c == 1:
+                out[name] = from_bits(bits).reshape(r)
+                continue
+            if name != "embed":
+                bits = bits.reshape(c // 64, r // 32, 4, 2, 32, 8).transpose(1, 4, 0, 3, 2, 5).reshape(r, c)
+            w = from_bits(np.ascontiguousarray(bits)).reshape(r, c)
+            if name.endswith("w_qkv"):
+                p = name[:-5]
+                out[p + "wq"], out[p + "wk"], out[p + "wv"] = w[:qd], w[qd:qd + kvd], w[qd + kvd:]
+            elif name.endswith("w_gu"):
+                p = name[:-4]
+                gu = w.reshape(r // 64, 2, 32, c)
+                out[p + "wg"], out[p + "wu"] = gu[:, 0].reshape(r // 2, c), gu[:, 1].reshape(r // 2, c)
+            elif name.endswith("w_o"):
+                out[name[:-3] + "wo"] = w
+            elif name.endswith("w_d"):
+                out[name[:-3] + "wd"] = w
+            else:
+                out[name] = w
+        return out
+
     def load_weights(self, src, nbytes=None):
         """src: numpy array (host) or an integer device/host address with nbytes."""
         if isinstance(src, np.ndarray):
@@ -300,6 +331,13 @@ def pl_kv_pack_host(pages_host, page_ids, k, v, first_pos, n_kv_heads, hd, page_
     assert pages_host.dtype == np.uint16 and pages_host.flags.c_contiguous
     _check(lib().pl_kv_pack_host(_np_ptr(pages_host), _np_ptr(page_ids), _np_ptr(k), _np_ptr(v), first_pos,
                                  k.shape[0], n_kv_heads, hd, page_tokens))
+
+
+def pl_debug_stream_read(ptr, nbytes, stream=0):
+    r = int(lib().pl_debug_stream_read(ptr, nbytes, stream))
+    if r < 0:
+        raise PlError(r, lib().pl_last_error().decode())
+    return r
 
 
 def pl_gemm_bf16(x, w, y, M, N, K, mode=0, splits=1, stream=0):

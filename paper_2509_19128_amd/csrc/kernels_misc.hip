@@ -130,6 +130,21 @@ __global__ void rope_append_kernel(const float *qkv, int splits, const float *cs
   }
 }
 
+// Read-only stream over a buffer (16-byte loads, 8 independent loads in flight per lane): measures
+// what HBM delivers to a kernel that does nothing but read.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ p, uint32_t *sink, int64_t n_per_wg) {
+  const uint4 *base = p + (int64_t)blockIdx.x * n_per_wg;
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  for (int64_t i = threadIdx.x; i < n_per_wg; i += 256 * 8) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = base[i + u * 256];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && sink) sink[0] = 1;   // keeps the loads alive
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -172,6 +187,14 @@ int launch_rope_append(const float *qkv, int splits, const float *cs, const int3
   hipLaunchKernelGGL(rope_append_kernel, dim3(Hq + 2 * Hkv, n), dim3(hd / 2), 0, s, qkv, splits, cs, pos, row_slot,
                      page_table, q_out, kv_layer, n, Hq, Hkv, hd, page_tokens, pages_per_seq);
   return ok();
+}
+
+int64_t launch_stream_read(const void *p, int64_t nbytes, uint32_t *sink, hipStream_t s) {
+  const int wgs = 8192;
+  int64_t n_per_wg = nbytes / 16 / wgs / 2048 * 2048;
+  if (n_per_wg <= 0) return 0;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(wgs), dim3(256), 0, s, (const uint4 *)p, sink, n_per_wg);
+  return hipGetLastError() == hipSuccess ? n_per_wg * 16 * wgs : -7;
 }
 
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s) {

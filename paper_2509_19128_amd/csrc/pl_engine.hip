@@ -819,6 +819,13 @@ int pl_gemm_bf16(const void *x, const void *w, void *y, int32_t M, int32_t N, in
   return PL_OK;
 }
 
+int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, void *stream) {
+  if (!device_ptr || nbytes < (int64_t)16 * 8192 * 2048) return fail(PL_E_INVAL, "need a device buffer of at least 256 MiB");
+  int64_t r = pl::launch_stream_read(device_ptr, nbytes, nullptr, (hipStream_t)stream);
+  if (r < 0) return fail(PL_E_HIP, "stream read launch failed");
+  return r;
+}
+
 int64_t pl_sample_workspace_bytes(int32_t n, int32_t vocab) {
   if (n < 1 || vocab < 1) return 0;
   return pl::sample_workspace_bytes(n, vocab);

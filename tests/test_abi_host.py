@@ -66,6 +66,17 @@ def test_weight_layout_matches_documented_order_and_size():
     assert np.array_equal(synth.bf16_bits_to_f32(blob[o:o + r * c]).reshape(r, c), synth.bf16_round(W["embed"]))
 
 
+def test_unpack_is_the_inverse_of_pack():
+    e = _engine()
+    W = synth.make_weights(M, 5)
+    U = e.unpack_weights(e.pack_weights(W, synth.f32_to_bf16_bits), synth.bf16_bits_to_f32)
+    assert set(U) == set(W)
+    for k in W:
+        assert np.array_equal(U[k], synth.bf16_round(W[k])), k
+    one = e.unpack_weights(e.pack_weights(W, synth.f32_to_bf16_bits), synth.bf16_bits_to_f32, names={"l1.w_gu"})
+    assert set(one) == {"l1.wg", "l1.wu"}
+
+
 @pytest.mark.parametrize("bad", [dict(head_dim=48), dict(n_q_heads=7), dict(d_model=320), dict(vocab=100),
                                  dict(n_kv_heads=0)])
 def test_create_rejects_unsupported_shapes(bad):
