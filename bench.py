@@ -220,7 +220,7 @@ def main():
 
     wl = Workload(eng, spec, model, seed=1234 + 3)
     wl.admit_steady_state()
-    eng.debug_set_profile(not args.no_profile)
+    eng.debug_set_profile(0 if args.no_profile else 1)   # events around the attention launches only
     for _ in range(args.warmup):
         wl.step()
     torch.cuda.synchronize()
@@ -249,6 +249,17 @@ def main():
     wall = time.perf_counter() - t0
     s1 = eng.stats()
 
+    # a short extra pass with events around every kernel group, for the time split only
+    split = None
+    if not args.no_profile:
+        eng.debug_set_profile(2)
+        a0 = eng.stats()
+        for _ in range(16):
+            wl.step()
+        a1 = eng.stats()
+        eng.debug_set_profile(1)
+        split = {k: (a1[k] - a0[k]) / 16 for k in ("attn_ms", "gemm_ms", "sample_ms", "other_ms")}
+
     d = {k: s1[k] - s0[k] for k in ("steps", "tokens_emitted", "slot_steps", "gpu_ms_total", "algorithmic_bytes",
                                      "attn_ms", "gemm_ms", "sample_ms", "other_ms", "attn_launches", "attn_kv_bytes")}
     sm = np.asarray(step_ms)
@@ -276,7 +287,7 @@ def main():
                      "frac_of_8TBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6 / HBM_PEAK_GBS},
         "swap": {"requested": swaps_requested, "flips_at_steps": flips, "stall_ms": stall_ms,
                  "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9},
-        "time_split_ms_per_step": {k: d[k] / max(d["steps"], 1) for k in ("attn_ms", "gemm_ms", "sample_ms", "other_ms")},
+        "time_split_ms_per_step": split,
     }
     res["hbm_read_stream_ceiling_GBs"] = stream_ceiling(torch, pl)
     if d["attn_launches"]:

@@ -182,9 +182,11 @@ int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_
 int pl_debug_add_sequence_at(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
                              int32_t max_new, float temperature, int32_t context_len,
                              int32_t n_emitted, int32_t last_token, int32_t *out_slot);
-/* Turn per-kernel-group timing on (1) or off (0): HIP events are recorded on the decode stream around
- * the attention, GEMM and sampler launches of every step and accumulated into pl_stats. */
-int pl_debug_set_profile(pl_engine *e, int32_t on);
+/* Per-kernel-group timing with HIP events recorded on the decode stream, accumulated into pl_stats:
+ * level 0 off; 1 around the attention launches only (attn_ms, attn_launches, attn_kv_bytes; everything
+ * else lands in other_ms); 2 around every group (attention, GEMMs, sampler, rest).  Each event costs a
+ * little GPU time between kernels, which is why level 1 exists. */
+int pl_debug_set_profile(pl_engine *e, int32_t level);
 /* Device pointer and size of the KV page pool (to fill it with synthetic values). */
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 

@@ -304,8 +304,8 @@ class Engine:
         k, v = np.ascontiguousarray(k, np.float32), np.ascontiguousarray(v, np.float32)
         _check(lib().pl_debug_write_kv(self._h, slot, layer, _np_ptr(k), _np_ptr(v), k.shape[0]))
 
-    def debug_set_profile(self, on):
-        _check(lib().pl_debug_set_profile(self._h, int(bool(on))))
+    def debug_set_profile(self, level):
+        _check(lib().pl_debug_set_profile(self._h, int(level)))
 
     def debug_kv_pool(self):
         p, n = C.c_void_p(), C.c_int64()

@@ -25,7 +25,8 @@ constexpr int LDS_ROW = 72;     // padded row length (elements) of the x tile in
 // completion) never waits for the younger W loads.
 template <int WM, int WN, int AT, int BT, int MODE>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
-                                                   void *__restrict__ Yv, int M, int N, int K, int ksteps) {
+                                                   void *__restrict__ Yv, int M, int N, int K, int ksteps,
+                                                   int n_base) {
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
   constexpr int XCH = BM * (BK / 8) / 256;       // 16-byte chunks of the x tile per thread
   static_assert(WM * WN == 4 && XCH >= 1, "tile");
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
   const int tid = threadIdx.x, l = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps W offsets in scalar registers
   const int wm = wave / WN, wn = wave % WN;
-  const int n0 = blockIdx.x * BN + wn * BT * 32;
+  const int n0 = n_base + blockIdx.x * BN + wn * BT * 32;
   const int m0 = blockIdx.z * BM;
   const int split = blockIdx.y;
   const int kbeg = split * ksteps * BK;
@@ -202,16 +203,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
   }
 }
 
+// Launch over output columns [n_begin, n_end) (multiples of the tile width, except the matrix edge).
 template <int WM, int WN, int AT, int BT>
 int launch_cfg(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,
-               hipStream_t s) {
+               int n_begin, int n_end, hipStream_t s) {
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
-  dim3 grid((N + BN - 1) / BN, splits, (M + BM - 1) / BM);
+  if (n_end <= n_begin) return 0;
+  dim3 grid((n_end - n_begin + BN - 1) / BN, splits, (M + BM - 1) / BM);
   int ksteps = 4 * ((K / (4 * BK) + splits - 1) / splits);
   if (mode == 0)
-    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 0>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps);
+    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 0>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin);
   else
-    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 1>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps);
+    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 1>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
@@ -237,10 +240,19 @@ int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, 
   if ((splits - 1) * ((K / (4 * BK) + splits - 1) / splits) >= K / (4 * BK)) return -1;   // an empty slice
   if (mode == 1 && (splits != 1 || N % 64)) return -1;
   if (mode != 0 && mode != 1) return -1;
-  if (M <= 32) return launch_cfg<1, 4, 1, 2>(x, w, y, M, N, K, mode, splits, s);
-  if (M <= 64) return launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, s);
-  if (M <= 128) return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, s);
-  return launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, s);
+  if (M <= 32) return launch_cfg<1, 4, 1, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
+  if (M <= 64) return launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
+  if (M <= 128) return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
+  // 256 x 128 tiles, one per compute unit and round.  When the tile count is a little over a
+  // multiple of 256 the last round would run on a few units at full length: those columns go to a
+  // second launch of 64-row tiles instead (4x the workgroups, each a quarter of the MFMA work).
+  const int tiles = ((N + 127) / 128) * ((M + 255) / 256), rem = tiles % 256;
+  if (M <= 256 && splits == 1 && tiles > 256 && rem > 0 && rem <= 64) {
+    const int n_main = (tiles - rem) * 128;
+    int rc = launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, 0, n_main, s);
+    return rc ? rc : launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, n_main, N, s);
+  }
+  return launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
 }
 
 }  // namespace pl

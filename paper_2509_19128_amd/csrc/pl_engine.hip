@@ -104,7 +104,7 @@ struct pl_engine {
   hipStream_t s_dec = nullptr, s_copy = nullptr;
   hipEvent_t ev_a = nullptr, ev_b = nullptr, ev_c = nullptr;
   // optional per-kernel-group timing: events[i] closes a segment of category cats[i]
-  bool profile = false;
+  int profile = 0;   // 0 off, 1 events around the attention launches only, 2 around every kernel group
   std::vector<hipEvent_t> prof_ev;
   std::vector<int> prof_cat;
   size_t prof_n = 0;
@@ -246,8 +246,8 @@ LayerW layer_weights(const pl_engine *e, int l) {
 enum { CAT_OTHER = 0, CAT_ATTN = 1, CAT_GEMM = 2, CAT_SAMPLE = 3 };
 
 // Close the segment of work enqueued since the previous mark and attribute it to `cat`.
-void mark(pl_engine *e, int cat) {
-  if (!e->profile) return;
+void mark(pl_engine *e, int cat, bool attention_edge = false) {
+  if (!e->profile || (e->profile == 1 && !attention_edge)) return;
   if (e->prof_n == e->prof_ev.size()) {
     hipEvent_t ev;
     if (hipEventCreate(&ev) != hipSuccess) return;
@@ -290,9 +290,9 @@ int enqueue_step(pl_engine *e, int n) {
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
     ap.max_chunks = e->attn_max_chunks;
     ap.work = e->attn_work; ap.max_items = e->attn_items;
-    mark(e, CAT_OTHER);
+    mark(e, CAT_OTHER, true);
     rc |= pl::launch_attention(ap, s);
-    mark(e, CAT_ATTN);
+    mark(e, CAT_ATTN, true);
     rc |= pl::launch_gemm(e->attn_out, w.w_o, e->parts, n, d, qd, 0, e->sp_o, s);
     mark(e, CAT_GEMM);
     rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_o, w.g2, e->a, n, d, c.rms_eps, s);
@@ -639,7 +639,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
         default: e->st.other_ms += ms;
       }
     }
-    if (e->prof_n) e->st.gemm_launches += 4 * (uint64_t)c.n_layers + 1;
+    if (e->prof_n && e->profile == 2) e->st.gemm_launches += 4 * (uint64_t)c.n_layers + 1;
     if (timed_stall) {
       float t_total = 0.f;
       HIP_TRY(hipEventElapsedTime(&t_total, e->ev_c, e->ev_a));
@@ -739,9 +739,9 @@ int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_
   return kv_xfer(e, slot, layer, nullptr, nullptr, k_in, v_in, n_ctx, true);
 }
 
-int pl_debug_set_profile(pl_engine *e, int32_t on) {
-  if (!e) return fail(PL_E_INVAL, "NULL argument");
-  e->profile = on != 0 && !e->dry;
+int pl_debug_set_profile(pl_engine *e, int32_t level) {
+  if (!e || level < 0 || level > 2) return fail(PL_E_INVAL, "bad argument");
+  e->profile = e->dry ? 0 : level;
   return PL_OK;
 }
 
