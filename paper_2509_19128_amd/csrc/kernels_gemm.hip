@@ -26,7 +26,7 @@ constexpr int LDS_ROW = 72;     // padded row length (elements) of the x tile in
 template <int WM, int WN, int AT, int BT, int MODE>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
                                                    void *__restrict__ Yv, int M, int N, int K, int ksteps,
-                                                   int n_base) {
+                                                   int n_base, int n_end, int nrow) {
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
   constexpr int XCH = BM * (BK / 8) / 256;       // 16-byte chunks of the x tile per thread
   static_assert(WM * WN == 4 && XCH >= 1, "tile");
@@ -35,8 +35,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
   const int tid = threadIdx.x, l = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps W offsets in scalar registers
   const int wm = wave / WN, wn = wave % WN;
-  const int n0 = n_base + blockIdx.x * BN + wn * BT * 32;
-  const int m0 = blockIdx.z * BM;
+  // Tile of this workgroup.  nrow = 0: (column tile, row tile) = (blockIdx.x, blockIdx.z).  nrow > 0:
+  // a flat grid in which the row tiles of one column tile sit 8 workgroup ids apart, so the hardware's
+  // round-robin deal of consecutive ids to the 8 XCDs puts them on the same XCD at the same moment
+  // and the second reader of a W tile finds it in that XCD's L2.
+  int ctile = blockIdx.x, rtile = blockIdx.z;
+  if (nrow > 0) {
+    rtile = (blockIdx.x >> 3) % nrow;
+    ctile = (blockIdx.x / (8 * nrow)) * 8 + (blockIdx.x & 7);
+    if (n_base + ctile * BN >= n_end) return;   // padding of the flat grid (uniform for the workgroup)
+  }
+  const int n0 = n_base + ctile * BN + wn * BT * 32;
+  const int m0 = rtile * BM;
   const int split = blockIdx.y;
   const int kbeg = split * ksteps * BK;
   const int nks = min(ksteps, K / BK - split * ksteps);
@@ -206,15 +216,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
 // Launch over output columns [n_begin, n_end) (multiples of the tile width, except the matrix edge).
 template <int WM, int WN, int AT, int BT>
 int launch_cfg(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,
-               int n_begin, int n_end, hipStream_t s) {
+               int n_begin, int n_end, hipStream_t s, bool paired = false) {
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
   if (n_end <= n_begin) return 0;
   dim3 grid((n_end - n_begin + BN - 1) / BN, splits, (M + BM - 1) / BM);
+  int nrow = 0;
+  if (paired) {   // flat grid, column tiles padded to a multiple of 8 (see the kernel)
+    nrow = grid.z;
+    grid.x = ((grid.x + 7) / 8) * 8 * nrow;
+    grid.z = 1;
+  }
   int ksteps = 4 * ((K / (4 * BK) + splits - 1) / splits);
   if (mode == 0)
-    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 0>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin);
+    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 0>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin,
+                       n_end, nrow);
   else
-    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 1>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin);
+    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 1>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin,
+                       n_end, nrow);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
@@ -243,15 +261,21 @@ int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, 
   if (M <= 32) return launch_cfg<1, 4, 1, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
   if (M <= 64) return launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
   if (M <= 128) return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
-  // 256 x 128 tiles, one per compute unit and round.  When the tile count is a little over a
-  // multiple of 256 the last round would run on a few units at full length: those columns go to a
-  // second launch of 64-row tiles instead (4x the workgroups, each a quarter of the MFMA work).
-  const int tiles = ((N + 127) / 128) * ((M + 255) / 256), rem = tiles % 256;
-  if (M <= 256 && splits == 1 && tiles > 256 && rem > 0 && rem <= 64) {
-    const int n_main = (tiles - rem) * 128;
-    int rc = launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, 0, n_main, s);
-    return rc ? rc : launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, n_main, N, s);
+  if (M <= 256 && splits == 1 && N >= 128 * 256) {
+    // Wide matrices without a K split: 128 x 256 tiles in XCD-local pairs.  Each wavefront owns its
+    // own 64 columns of W (no fragment is loaded twice by one workgroup) and the x tile is half as
+    // tall, which cuts the vector-memory and LDS-store traffic per MFMA; the second row tile reads W
+    // from L2.  When the tile count is a little over a multiple of 256 the last round would run on a
+    // few units at full length: those columns go to a second launch of 64 x 128 tiles instead.
+    const int ctiles = (N + 255) / 256, tiles = 2 * ctiles, rem = tiles % 256;
+    if (tiles > 256 && rem > 0 && rem <= 64) {
+      const int n_main = ((tiles - rem) / 2) * 256;
+      int rc = launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, n_main, s, true);
+      return rc ? rc : launch_cfg<2, 2, 1, 2>(x, w, y, M, N, K, mode, splits, n_main, N, s);
+    }
+    return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s, true);
   }
+  // otherwise 256 x 128 tiles, one per compute unit and round
   return launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
 }
 

@@ -112,7 +112,8 @@ def test_attention_full_microbench_shape_on_sampled_rows():
 
 GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 1024, 4), (3, 256, 1024, 2), (33, 320, 256, 1), (64, 2048, 1536, 3),
                (130, 1536, 8960, 7), (256, 4608, 3584, 7), (200, 3584, 18944, 8), (256, 3584, 18944, 9), (256, 2560, 3584, 1),
-               (300, 640, 512, 2), (256, 33792, 256, 1), (130, 34000 // 32 * 32, 256, 1)]
+               (300, 640, 512, 2), (256, 33792, 256, 1), (130, 34000 // 32 * 32, 256, 1),
+               (256, 43552, 256, 1), (129, 32768, 512, 1)]   # the last four take the paired 128 x 256 tiles
 
 
 @pytest.mark.parametrize("M,N,K,splits", GEMM_SHAPES)
@@ -130,7 +131,8 @@ def test_gemm_partials_sum_to_the_product(M, N, K, splits):
     assert ok, err
 
 
-@pytest.mark.parametrize("M,F,K", [(4, 1024, 256), (64, 2240, 1536), (256, 1280, 3584), (129, 320, 512), (200, 16640, 256)])
+@pytest.mark.parametrize("M,F,K", [(4, 1024, 256), (64, 2240, 1536), (256, 1280, 3584), (129, 320, 512), (200, 16640, 256),
+                                   (200, 18944, 256)])
 def test_gemm_swiglu_epilogue(M, F, K):
     rng = np.random.default_rng(F + M)
     x = synth.bf16_round(rng.standard_normal((M, K)).astype(np.float32))
