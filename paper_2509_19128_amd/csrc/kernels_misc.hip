@@ -52,9 +52,15 @@ __global__ __launch_bounds__(256) void resid_rmsnorm_kernel(float *h, const floa
     const int idx = threadIdx.x + it * 256;
     if (idx < d4) {
       float4 x = h4[idx];
-      for (int s = 0; s < splits; ++s) {
-        const float4 p = ((const float4 *)(parts + ((int64_t)s * n + row) * d))[idx];
-        x.x += p.x; x.y += p.y; x.z += p.z; x.w += p.w;
+      // loads of up to 8 slices are issued together, the adds stay in slice order
+      for (int s0 = 0; s0 < splits; s0 += 8) {
+        float4 p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (s0 + u < splits) p[u] = ((const float4 *)(parts + ((int64_t)(s0 + u) * n + row) * d))[idx];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (s0 + u < splits) { x.x += p[u].x; x.y += p[u].y; x.z += p[u].z; x.w += p[u].w; }
       }
       h4[idx] = x;
       v[it] = x;
@@ -102,10 +108,19 @@ __global__ void rope_append_kernel(const float *qkv, int splits, const float *cs
   const int half = hd / 2;
   const int width = (Hq + 2 * Hkv) * hd;
   float x1 = 0.f, x2 = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const float *src = qkv + ((int64_t)s * n + row) * width + hh * hd;
-    x1 += src[i];
-    x2 += src[half + i];
+  // loads of up to 8 slices are issued together, the adds stay in slice order
+  for (int s0 = 0; s0 < splits; s0 += 8) {
+    float p1[8], p2[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < splits) {
+        const float *src = qkv + ((int64_t)(s0 + u) * n + row) * width + hh * hd;
+        p1[u] = src[i];
+        p2[u] = src[half + i];
+      }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < splits) { x1 += p1[u]; x2 += p2[u]; }
   }
   if (hh < Hq) {
     const float c = cs[(int64_t)row * hd + i], sn = cs[(int64_t)row * hd + half + i];
