@@ -79,8 +79,8 @@ class Workload:
     """Alg. 2's Actor loop around the engine: pop finished, refill to H, request a weight update every
     `swap_every` steps, generate next tokens."""
 
-    def __init__(self, eng, spec, model, seed):
-        self.eng, self.spec, self.model = eng, spec, model
+    def __init__(self, eng, spec, model, seed, batched_prefill=True):
+        self.eng, self.spec, self.model, self.batched_prefill = eng, spec, model, batched_prefill
         self.rng = np.random.default_rng(seed)
         self.next_id = 0
 
@@ -89,14 +89,16 @@ class Workload:
 
     def admit_steady_state(self):
         """Fill every slot with a sequence at a random point of its life, drawn from the stationary law of
-        constant-batch refill (busy time of a slot is proportional to prompt + length - 1)."""
+        constant-batch refill: a slot is busy for prompt + length - 1 steps when the prompt is read one
+        token per step, for `length` steps when it is read in batched passes at admission."""
         B, P = self.spec["batch"], self.spec["prompt"]
         cand = synth.lognormal_lengths(self.rng, 200_000, self.spec["mean"], 1, self.spec["gmax"])
-        busy = cand + P - 1
+        first = P - 1 if self.batched_prefill else 0
+        busy = cand + P - 1 - first
         g = self.rng.choice(cand, size=B, p=busy / busy.sum())
         for i in range(B):
             G = int(g[i])
-            pos = int(self.rng.integers(0, P + G - 1))
+            pos = int(self.rng.integers(first, P + G - 1))
             prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
             self.eng.debug_add_sequence_at(self.next_id, prompt, P, G, 1.0, pos, max(0, pos - (P - 1)),
                                            int(self.rng.integers(0, self.model.vocab)))
@@ -106,7 +108,9 @@ class Workload:
         P = self.spec["prompt"]
         while self.eng.num_active() < self.spec["batch"]:
             prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
-            self.eng.add_sequence(self.next_id, prompt, self._new_len(), 1.0)
+            slot = self.eng.add_sequence(self.next_id, prompt, self._new_len(), 1.0)
+            if self.batched_prefill:
+                self.eng.prefill(slot)
             self.next_id += 1
 
     def step(self):
@@ -187,6 +191,8 @@ def main():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
+    ap.add_argument("--prefill", default="batched", choices=["batched", "decode"],
+                    help="how a refilled slot reads its prompt: batched passes at admission, or one token per decode step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not record per-kernel HIP events")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -218,7 +224,7 @@ def main():
     torch.cuda.empty_cache()
     fill_kv_pool(eng, torch, seed=1239)
 
-    wl = Workload(eng, spec, model, seed=1234 + 3)
+    wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill=args.prefill == "batched")
     wl.admit_steady_state()
     eng.debug_set_profile(0 if args.no_profile else 1)   # events around the attention launches only
     for _ in range(args.warmup):
@@ -277,7 +283,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}-shaped decoder, constant batch {spec['batch']} with continuous refill, "
                                f"{spec['prompt']}-token prompts, lognormal(mean {spec['mean']:.0f}, sigma 0.75, max {spec['gmax']}) "
-                               f"generation lengths, steady-state ages, weight update from pinned host every {spec['swap_every']} steps",
+                               f"generation lengths, steady-state ages, weight update from pinned host every {spec['swap_every']} steps, "
+                               f"prompts read {'in batched passes at admission' if args.prefill == 'batched' else 'one token per step'}",
                    "mean_context": d["algorithmic_bytes"] and float((d["attn_kv_bytes"] / max(d["attn_launches"], 1)) /
                                                                     (4.0 * model.n_kv_heads * model.head_dim) / spec["batch"]),
                    "slot_utilisation": d["tokens_emitted"] / max(d["slot_steps"], 1)},
@@ -288,6 +295,8 @@ def main():
         "swap": {"requested": swaps_requested, "flips_at_steps": flips, "stall_ms": stall_ms,
                  "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9},
         "time_split_ms_per_step": split,
+        "prefill": {"mode": args.prefill, "positions": s1["prefill_positions"] - s0["prefill_positions"],
+                    "passes": s1["prefill_passes"] - s0["prefill_passes"], "gpu_ms": s1["prefill_ms"] - s0["prefill_ms"]},
     }
     res["hbm_read_stream_ceiling_GBs"] = stream_ceiling(torch, pl)
     if d["attn_launches"]:

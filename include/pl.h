@@ -94,6 +94,9 @@ typedef struct {
   double attn_ms, gemm_ms, sample_ms, other_ms;
   uint64_t attn_launches, gemm_launches; /* attention launches (one per layer per step), GEMM launches */
   double attn_kv_bytes;                  /* K/V bytes those attention launches had to read */
+  /* batched prompt reading (pl_prefill); not part of steps / slot_steps / gpu_ms_total above */
+  uint64_t prefill_passes, prefill_positions;
+  double prefill_ms;
 } pl_stats;
 
 /* ---- engine life cycle --------------------------------------------------------------------- */
@@ -151,6 +154,16 @@ int pl_swap_poll(pl_engine *e, int32_t *staged_ready, uint32_t *active_version);
  * token out of range. */
 int pl_add_sequence(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
                     int32_t max_new, float temperature, int32_t *out_slot);
+/* Batched prompt reading on refill ("add prompts", Alg. 2): reads the positions of the slot's prompt
+ * that have not been read yet, except the last one, in passes of up to min(max_batch, 256) positions
+ * through the same kernels as a decode step (rows = consecutive positions of one sequence, causal
+ * because row i attends to positions <= its own), under the active weights.  It leaves exactly the
+ * keys and values that reading those tokens one per step would leave (up to bf16 rounding of
+ * identical arithmetic: same kernels, same per-row operation order) and emits nothing; the next
+ * pl_decode_step reads the last prompt token and produces the first generated token.
+ * *out_positions (may be NULL) receives the number of positions read (0 if none were left).
+ * Blocks until done.  PL_E_STATE if the slot is idle or before pl_load_weights. */
+int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions);
 /* Free a slot and its KV pages (finished or not).  PL_E_STATE if the slot is idle. */
 int pl_retire_sequence(pl_engine *e, int32_t slot);
 int32_t pl_num_active(const pl_engine *e);

@@ -20,7 +20,7 @@ PL_DEVICE_NONE = -1
 # every symbol include/pl.h declares
 EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
-    "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_retire_sequence",
+    "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
     "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample",
@@ -55,7 +55,8 @@ class Stats(C.Structure):
                 ("last_swap_copy_ms", C.c_float), ("active_version", C.c_uint32),
                 ("kv_pages_free", C.c_int64), ("kv_pages_total", C.c_int64),
                 ("attn_ms", C.c_double), ("gemm_ms", C.c_double), ("sample_ms", C.c_double), ("other_ms", C.c_double),
-                ("attn_launches", C.c_uint64), ("gemm_launches", C.c_uint64), ("attn_kv_bytes", C.c_double)]
+                ("attn_launches", C.c_uint64), ("gemm_launches", C.c_uint64), ("attn_kv_bytes", C.c_double),
+                ("prefill_passes", C.c_uint64), ("prefill_positions", C.c_uint64), ("prefill_ms", C.c_double)]
 
 
 _lib = None
@@ -88,6 +89,7 @@ def lib():
         "pl_swap_weights": (C.c_int, [vp, vp, i64, u32, P(u32)]),
         "pl_swap_poll": (C.c_int, [vp, P(i32), P(u32)]),
         "pl_add_sequence": (C.c_int, [vp, u64, vp, i32, i32, f32, P(i32)]),
+        "pl_prefill": (C.c_int, [vp, i32, P(i32)]),
         "pl_retire_sequence": (C.c_int, [vp, i32]),
         "pl_num_active": (i32, [vp]),
         "pl_decode_step": (C.c_int, [vp, vp, P(StepOut)]),
@@ -266,6 +268,12 @@ class Engine:
         _check(lib().pl_debug_add_sequence_at(self._h, seq_id, None if p is None else _np_ptr(p), n_prompt, max_new,
                                               temperature, context_len, n_emitted, last_token, C.byref(s)))
         return s.value
+
+    def prefill(self, slot):
+        """Read the slot's prompt except its last token in batched passes; returns the positions read."""
+        n = C.c_int32()
+        _check(lib().pl_prefill(self._h, slot, C.byref(n)))
+        return n.value
 
     def retire_sequence(self, slot):
         _check(lib().pl_retire_sequence(self._h, slot))

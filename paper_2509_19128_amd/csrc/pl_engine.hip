@@ -258,7 +258,9 @@ void mark(pl_engine *e, int cat, bool attention_edge = false) {
   (void)hipEventRecord(e->prof_ev[e->prof_n++], e->s_dec);
 }
 
-int enqueue_step(pl_engine *e, int n) {
+// prefill: rows are consecutive prompt positions of one slot; only the keys and values they leave in the
+// cache are wanted, so the last layer stops after its append and there is no LM head or sampler.
+int enqueue_step(pl_engine *e, int n, bool prefill = false) {
   const pl_model_cfg &c = e->cfg;
   hipStream_t s = e->s_dec;
   e->prof_n = 0;
@@ -290,6 +292,7 @@ int enqueue_step(pl_engine *e, int n) {
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
     ap.max_chunks = e->attn_max_chunks;
     ap.work = e->attn_work; ap.max_items = e->attn_items;
+    if (prefill && l + 1 == c.n_layers) break;
     mark(e, CAT_OTHER, true);
     rc |= pl::launch_attention(ap, s);
     mark(e, CAT_ATTN, true);
@@ -304,6 +307,7 @@ int enqueue_step(pl_engine *e, int n) {
     rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_d, g_next, e->a, n, d, c.rms_eps, s);
   }
   mark(e, CAT_OTHER);
+  if (prefill) return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
   rc |= pl::launch_gemm(e->a, lm, e->logits, n, c.vocab, d, 0, 1, s);
   mark(e, CAT_GEMM);
   pl::SampleParams sp{};
@@ -673,6 +677,63 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   e->st.gpu_ms_total += out->step_ms;
   const double kvb = 2.0 * c.n_layers * c.n_kv_heads * c.head_dim * 2.0;
   e->st.algorithmic_bytes += (double)e->streamed_weight_bytes + (kv_tokens + n) * kvb;
+  return PL_OK;
+}
+
+int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  if (out_positions) *out_positions = 0;
+  if (!e->loaded) return fail(PL_E_STATE, "no weights loaded");
+  const pl_model_cfg &c = e->cfg;
+  if (slot < 0 || slot >= c.max_batch || !e->seqs[slot].active) return fail(PL_E_STATE, "slot %d is idle", slot);
+  Seq &q = e->seqs[slot];
+  const int first = q.pos, last = q.n_prompt - 1;   // positions [first, last) are read here
+  if (first >= last) return PL_OK;
+  if ((int)q.prompt.size() < q.n_prompt) return fail(PL_E_STATE, "slot %d holds no prompt", slot);
+  if ((int64_t)q.pages.size() * e->page_tokens < last) return fail(PL_E_STATE, "slot %d has no pages for its prompt", slot);
+  const int rows_max = std::min<int>(c.max_batch, 256);
+  int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
+  float *inv_t = e->m_inv_t(false);
+  uint64_t *sid = e->m_seq_id(false);
+  if (!e->dry) HIP_TRY(hipSetDevice(c.device));
+  for (int p0 = first; p0 < last; p0 += rows_max) {
+    const int n = std::min(rows_max, last - p0);
+    int items = 0;
+    for (int r = 0; r < n; ++r) {
+      row_slot[r] = slot;
+      pos[r] = p0 + r;
+      inp[r] = q.prompt[p0 + r];
+      frc[r] = -1;
+      inv_t[r] = q.inv_t;
+      sid[r] = q.seq_id;
+      items += (p0 + r + 1 + e->attn_chunk - 1) / e->attn_chunk;
+    }
+    e->attn_items = items;
+    if (!e->dry) {
+      hipStream_t s = e->s_dec;
+      if (e->pt_dirty) {
+        HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
+        e->pt_dirty = false;
+      }
+      HIP_TRY(hipMemcpyAsync(e->meta_d, e->meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
+      HIP_TRY(hipEventRecord(e->ev_a, s));
+      const int prof = e->profile;
+      e->profile = 0;   // the per-group timers describe decode steps only
+      int rc = enqueue_step(e, n, true);
+      e->profile = prof;
+      if (rc) return rc;
+      HIP_TRY(hipEventRecord(e->ev_b, s));
+      HIP_TRY(hipStreamSynchronize(s));   // the host metadata image is reused by the next pass
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, e->ev_a, e->ev_b));
+      e->st.prefill_ms += ms;
+    }
+    e->st.prefill_passes++;
+    e->st.prefill_positions += n;
+  }
+  q.pos = last;
+  e->last_n = 0;
+  if (out_positions) *out_positions = last - first;
   return PL_OK;
 }
 

@@ -199,3 +199,27 @@ def test_mid_flight_admission_hook():
     assert r["position"][0] == 70 and r["emitted"][0] == 1
     with pytest.raises(pl.PlError):
         e.debug_add_sequence_at(10, None, 16, 64, 1.0, context_len=5, n_emitted=0, last_token=3)  # prompt needed
+
+
+def test_batched_prefill_bookkeeping():
+    """pl_prefill reads all prompt positions but the last; the next step reads that one and emits."""
+    e = _loaded()
+    s0 = e.add_sequence(1, [5, 6, 7, 8, 9, 10, 11], 10)
+    s1 = e.add_sequence(2, [4], 10)
+    assert e.prefill(s0) == 6 and e.prefill(s0) == 0             # nothing left the second time
+    assert e.prefill(s1) == 0                                    # a one-token prompt has nothing to prefill
+    st = e.stats()
+    assert st["prefill_positions"] == 6 and st["prefill_passes"] == 2   # passes of min(max_batch, 256) = 4 rows
+    assert st["steps"] == 0 and st["tokens_emitted"] == 0
+    r = e.decode_step()
+    assert r["n"] == 2 and r["position"].tolist() == [6, 0] and r["emitted"].tolist() == [1, 1]
+    with pytest.raises(pl.PlError) as ex:
+        e.prefill(3)                                             # idle slot
+    assert ex.value.code == pl.PL_E_STATE
+    # a partly read prompt: two steps one token at a time, then the rest in one go
+    s2 = e.add_sequence(3, list(range(10, 20)), 2)
+    e.decode_step(); e.decode_step()
+    assert e.prefill(s2) == 7
+    r = e.decode_step()
+    i = r["slot"].tolist().index(s2)
+    assert r["position"][i] == 9 and r["emitted"][i] == 1

@@ -250,3 +250,99 @@ def test_one_layer_slice_of_the_large_shapes(name, batch, ctx):
                 assert float((lg[i] - ref).std()) <= 1e-2 * float(ref.std()), (s, i)
                 assert abs(o["logprob"][i] - r.logprob) <= ATOL * scale + RTOL * abs(r.logprob)
     eng.close()
+
+
+# ---- batched prompt reading on refill ---------------------------------------------------------------
+
+def _kv_of(eng, slot, n_ctx):
+    return [eng.debug_read_kv(slot, l, n_ctx) for l in range(M.n_layers)]
+
+
+@pytest.mark.parametrize("n_prompt", [2, 5, 33, 100])
+def test_batched_prefill_leaves_the_cache_of_reading_the_prompt_token_by_token(weights, n_prompt):
+    """Against the oracle (which reads prompts one token per step, the definition): keys and values of
+    every layer after pl_prefill, then the logits of the step that reads the last prompt token and the
+    following steps.  Against the engine's own token-by-token path the cache must be bit-identical:
+    the same kernels run with the same per-row operation order, only the row set differs."""
+    master, _ = weights
+    blob = None
+    prompts = synth.random_prompts(np.random.default_rng(n_prompt), 3, n_prompt, M.vocab)
+    orc = OracleEngine(M, _rounded(master), max_batch=4, seed=SEED)
+    eng_b, eng_s = _engine(), _engine()
+    for e in (eng_b, eng_s):
+        blob = e.pack_weights(master, synth.f32_to_bf16_bits)
+        e.load_weights(blob)
+    for i in range(3):
+        for e in (orc, eng_b, eng_s):
+            assert e.add_sequence(50 + i, prompts[i], 6) == i
+    for i in range(3):
+        assert eng_b.prefill(i) == n_prompt - 1
+    for _ in range(n_prompt - 1):
+        orc.decode_step()
+        eng_s.decode_step()
+    for i in range(3):
+        kv_b, kv_s = _kv_of(eng_b, i, n_prompt - 1), _kv_of(eng_s, i, n_prompt - 1)
+        for l in range(M.n_layers):
+            assert np.array_equal(kv_b[l][0], kv_s[l][0]) and np.array_equal(kv_b[l][1], kv_s[l][1]), (i, l)
+            ok, err = close(kv_b[l][0], np.asarray(orc.slots[i].cache.k[l][:n_prompt - 1]), ATOL, RTOL)
+            assert ok, ("K", i, l, err)
+            ok, err = close(kv_b[l][1], np.asarray(orc.slots[i].cache.v[l][:n_prompt - 1]), ATOL, RTOL)
+            assert ok, ("V", i, l, err)
+    # the steps after it: teacher-forced against the oracle, bit-identical between the two engines
+    for step in range(6):
+        recs = orc.decode_step()
+        forced = np.full(4, -1, np.int32)
+        for r in recs:
+            forced[r.slot] = r.token
+        ob, os_ = eng_b.decode_step(forced), eng_s.decode_step(forced)
+        lb, ls = eng_b.debug_get_logits(ob["n"]), eng_s.debug_get_logits(os_["n"])
+        assert np.array_equal(lb, ls) and np.array_equal(ob["logprob"], os_["logprob"])
+        for i, r in enumerate(recs):
+            assert (ob["position"][i], bool(ob["emitted"][i]), bool(ob["finished"][i])) == (r.position, r.emitted, r.finished)
+            ok, err = close(lb[i], orc.last_logits[r.slot], ATOL, RTOL)
+            assert ok, (step, i, err)
+    assert eng_b.stats()["prefill_positions"] == 3 * (n_prompt - 1)
+    eng_b.close(); eng_s.close()
+
+
+def test_batched_prefill_under_the_weights_active_at_admission_then_a_swap(weights):
+    """A sequence admitted after an update reads its prompt under the new weights, while its
+    neighbour keeps the cache computed under the old ones (Sec. 5.1)."""
+    master, pert = weights
+    orc = OracleEngine(M, _rounded(master), max_batch=4, seed=SEED)
+    eng = _engine()
+    blobs = [eng.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
+    eng.load_weights(blobs[0])
+    prompts = synth.random_prompts(np.random.default_rng(9), 2, 20, M.vocab)
+    for e in (orc, eng):
+        e.add_sequence(1, prompts[0], 30)
+    eng.prefill(0)
+    for _ in range(19):
+        orc.decode_step()
+    def both_step():
+        recs = orc.decode_step()
+        forced = np.full(4, -1, np.int32)
+        for r in recs:
+            forced[r.slot] = r.token
+        out = eng.decode_step(forced)
+        lg = eng.debug_get_logits(out["n"])
+        for i, r in enumerate(recs):
+            assert out["weight_version"][i] == r.weight_version and out["position"][i] == r.position
+            ok, err = close(lg[i], orc.last_logits[r.slot], ATOL, RTOL)
+            assert ok, (r.slot, r.position, err)
+    for _ in range(5):
+        both_step()
+    orc.swap_weights(_rounded(pert))
+    eng.swap_weights(blobs[1], flags=pl.PL_SWAP_WAIT)
+    both_step()                                   # the flip happens at this step boundary
+    for e in (orc, eng):
+        e.add_sequence(2, prompts[1], 10)
+    eng.prefill(1)
+    for _ in range(19):                           # the oracle reads the new prompt token by token; slot 0 must wait
+        seq0 = orc.slots[0]
+        orc.slots[0] = None
+        orc.decode_step()
+        orc.slots[0] = seq0
+    for _ in range(6):
+        both_step()
+    eng.close()
