@@ -79,8 +79,9 @@ class Workload:
     """Alg. 2's Actor loop around the engine: pop finished, refill to H, request a weight update every
     `swap_every` steps, generate next tokens."""
 
-    def __init__(self, eng, spec, model, seed, batched_prefill=True):
+    def __init__(self, eng, spec, model, seed, batched_prefill=True, keep_history=False):
         self.eng, self.spec, self.model, self.batched_prefill = eng, spec, model, batched_prefill
+        self.keep_history = keep_history
         self.rng = np.random.default_rng(seed)
         self.next_id = 0
 
@@ -100,8 +101,11 @@ class Workload:
             G = int(g[i])
             pos = int(self.rng.integers(first, P + G - 1))
             prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
-            self.eng.debug_add_sequence_at(self.next_id, prompt, P, G, 1.0, pos, max(0, pos - (P - 1)),
-                                           int(self.rng.integers(0, self.model.vocab)))
+            slot = self.eng.debug_add_sequence_at(self.next_id, prompt, P, G, 1.0, pos, max(0, pos - (P - 1)),
+                                                  int(self.rng.integers(0, self.model.vocab)))
+            if self.keep_history:   # tokens "read so far", so that the cache can be recomputed after an update
+                hist = np.concatenate([prompt, self.rng.integers(0, self.model.vocab, max(0, pos - P))])[:pos]
+                self.eng.debug_set_history(slot, hist)
             self.next_id += 1
 
     def refill(self):
@@ -193,6 +197,8 @@ def main():
     ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
     ap.add_argument("--prefill", default="batched", choices=["batched", "decode"],
                     help="how a refilled slot reads its prompt: batched passes at admission, or one token per decode step")
+    ap.add_argument("--recompute-kv", action="store_true",
+                    help="weight updates rebuild every sequence's KV cache under the new weights (Sec. 5.1 variant; slow)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not record per-kernel HIP events")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -224,7 +230,7 @@ def main():
     torch.cuda.empty_cache()
     fill_kv_pool(eng, torch, seed=1239)
 
-    wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill=args.prefill == "batched")
+    wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill=args.prefill == "batched", keep_history=args.recompute_kv)
     wl.admit_steady_state()
     eng.debug_set_profile(0 if args.no_profile else 1)   # events around the attention launches only
     for _ in range(args.warmup):
@@ -239,7 +245,7 @@ def main():
     for k in range(args.steps):
         if spec["swap_every"] and k % spec["swap_every"] == spec["swap_every"] // 2:
             try:    # Alg. 2: the trainer requests an update; the engine stages it while decoding goes on
-                eng.swap_weights(host[swaps_requested % 2].data_ptr(), eng.weight_nbytes(), flags=pl.PL_SWAP_ASYNC)
+                eng.swap_weights(host[swaps_requested % 2].data_ptr(), eng.weight_nbytes(), flags=pl.PL_SWAP_ASYNC | (pl.PL_SWAP_RECOMPUTE_KV if args.recompute_kv else 0))
                 swaps_requested += 1
             except pl.PlError as ex:
                 if ex.code != pl.PL_E_BUSY:
@@ -293,7 +299,11 @@ def main():
                      "achieved_GBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6,
                      "frac_of_8TBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6 / HBM_PEAK_GBS},
         "swap": {"requested": swaps_requested, "flips_at_steps": flips, "stall_ms": stall_ms,
-                 "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9},
+                 "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9,
+                 "kv_cache": "recomputed at the flip" if args.recompute_kv else "kept",
+                 "recompute_positions": s1["recompute_positions"] - s0["recompute_positions"],
+                 "recompute_passes": s1["recompute_passes"] - s0["recompute_passes"],
+                 "recompute_gpu_ms": s1["recompute_ms"] - s0["recompute_ms"]},
         "time_split_ms_per_step": split,
         "prefill": {"mode": args.prefill, "positions": s1["prefill_positions"] - s0["prefill_positions"],
                     "passes": s1["prefill_passes"] - s0["prefill_passes"], "gpu_ms": s1["prefill_ms"] - s0["prefill_ms"]},

@@ -41,6 +41,7 @@ typedef enum {
 
 #define PL_SWAP_ASYNC 0u /* stage in the background; flip at the first step boundary once staged */
 #define PL_SWAP_WAIT 1u  /* the next step waits for the staging copy, then flips                  */
+#define PL_SWAP_RECOMPUTE_KV 2u /* or-ed in: at the flip, rebuild every sequence's cache under the new weights */
 #define PL_DEVICE_NONE (-1) /* bookkeeping-only engine: no GPU is touched, no token is computed  */
 
 typedef struct pl_engine pl_engine;
@@ -97,6 +98,10 @@ typedef struct {
   /* batched prompt reading (pl_prefill); not part of steps / slot_steps / gpu_ms_total above */
   uint64_t prefill_passes, prefill_positions;
   double prefill_ms;
+  /* cache recomputation after updates staged with PL_SWAP_RECOMPUTE_KV (its time is also part of
+   * that step's swap_stall_ms) */
+  uint64_t recompute_passes, recompute_positions;
+  double recompute_ms;
 } pl_stats;
 
 /* ---- engine life cycle --------------------------------------------------------------------- */
@@ -139,7 +144,13 @@ int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes);
  * src must stay valid and unmodified until the flip.  *out_new_version receives the version the
  * new weights will carry.  PL_E_BUSY if an update is already staged and not yet active;
  * PL_E_STATE before pl_load_weights.  With n_weight_buffers == 1 the copy overwrites the active
- * buffer on the decode stream and the call returns when it is done. */
+ * buffer on the decode stream and the call returns when it is done.
+ * flags | PL_SWAP_RECOMPUTE_KV selects the "KV cache recomputed" variant of Sec. 5.1 instead: at the
+ * flip, before the step produces anything, every token each occupied slot has read so far is replayed
+ * under the new weights (batched passes through the decode kernels) and its keys and values are
+ * overwritten in place, so later tokens are conditioned on a fresh cache.  The time is reported in that
+ * step's swap_stall_ms and in pl_stats.recompute_ms.  PL_E_STATE if a slot was admitted mid-life
+ * without its token history (pl_debug_add_sequence_at without pl_debug_set_history). */
 int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flags,
                     uint32_t *out_new_version);
 int pl_swap_poll(pl_engine *e, int32_t *staged_ready, uint32_t *active_version);
@@ -195,6 +206,9 @@ int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_
 int pl_debug_add_sequence_at(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
                              int32_t max_new, float temperature, int32_t context_len,
                              int32_t n_emitted, int32_t last_token, int32_t *out_slot);
+/* Tokens read at positions [0, n) of a slot admitted with pl_debug_add_sequence_at (n must equal its
+ * context length), so that its cache can be recomputed after an update. */
+int pl_debug_set_history(pl_engine *e, int32_t slot, const int32_t *tokens, int32_t n);
 /* Per-kernel-group timing with HIP events recorded on the decode stream, accumulated into pl_stats:
  * level 0 off; 1 around the attention launches only (attn_ms, attn_launches, attn_kv_bytes; everything
  * else lands in other_ms); 2 around every group (attention, GEMMs, sampler, rest).  Each event costs a

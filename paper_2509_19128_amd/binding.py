@@ -8,13 +8,13 @@ import numpy as np
 
 __all__ = [
     "PL_OK", "PL_E_INVAL", "PL_E_NOSLOT", "PL_E_NOKV", "PL_E_BUSY", "PL_E_STATE", "PL_E_CTX", "PL_E_HIP",
-    "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_DEVICE_NONE", "PlError", "ModelCfg", "StepOut", "Stats",
+    "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_SWAP_RECOMPUTE_KV", "PL_DEVICE_NONE", "PlError", "ModelCfg", "StepOut", "Stats",
     "lib", "library_path", "Engine", "operand_order", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
     "pl_gemm_bf16", "pl_sample", "pl_sample_workspace_bytes", "pl_debug_stream_read", "EXPORTS",
 ]
 
 PL_OK, PL_E_INVAL, PL_E_NOSLOT, PL_E_NOKV, PL_E_BUSY, PL_E_STATE, PL_E_CTX, PL_E_HIP, PL_E_NOMEM = 0, -1, -2, -3, -4, -5, -6, -7, -8
-PL_SWAP_ASYNC, PL_SWAP_WAIT = 0, 1
+PL_SWAP_ASYNC, PL_SWAP_WAIT, PL_SWAP_RECOMPUTE_KV = 0, 1, 2
 PL_DEVICE_NONE = -1
 
 # every symbol include/pl.h declares
@@ -22,7 +22,7 @@ EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
     "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
-    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
+    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample",
 ]
 
@@ -56,7 +56,8 @@ class Stats(C.Structure):
                 ("kv_pages_free", C.c_int64), ("kv_pages_total", C.c_int64),
                 ("attn_ms", C.c_double), ("gemm_ms", C.c_double), ("sample_ms", C.c_double), ("other_ms", C.c_double),
                 ("attn_launches", C.c_uint64), ("gemm_launches", C.c_uint64), ("attn_kv_bytes", C.c_double),
-                ("prefill_passes", C.c_uint64), ("prefill_positions", C.c_uint64), ("prefill_ms", C.c_double)]
+                ("prefill_passes", C.c_uint64), ("prefill_positions", C.c_uint64), ("prefill_ms", C.c_double),
+                ("recompute_passes", C.c_uint64), ("recompute_positions", C.c_uint64), ("recompute_ms", C.c_double)]
 
 
 _lib = None
@@ -90,6 +91,7 @@ def lib():
         "pl_swap_poll": (C.c_int, [vp, P(i32), P(u32)]),
         "pl_add_sequence": (C.c_int, [vp, u64, vp, i32, i32, f32, P(i32)]),
         "pl_prefill": (C.c_int, [vp, i32, P(i32)]),
+        "pl_debug_set_history": (C.c_int, [vp, i32, vp, i32]),
         "pl_retire_sequence": (C.c_int, [vp, i32]),
         "pl_num_active": (i32, [vp]),
         "pl_decode_step": (C.c_int, [vp, vp, P(StepOut)]),
@@ -274,6 +276,10 @@ class Engine:
         n = C.c_int32()
         _check(lib().pl_prefill(self._h, slot, C.byref(n)))
         return n.value
+
+    def debug_set_history(self, slot, tokens):
+        t = np.ascontiguousarray(tokens, np.int32)
+        _check(lib().pl_debug_set_history(self._h, slot, _np_ptr(t), t.size))
 
     def retire_sequence(self, slot):
         _check(lib().pl_retire_sequence(self._h, slot))

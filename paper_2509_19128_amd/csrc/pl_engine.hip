@@ -55,6 +55,8 @@ struct Seq {
   bool active = false;
   uint64_t seq_id = 0;
   std::vector<int32_t> prompt;
+  std::vector<int32_t> hist;   // tokens read at positions [0, pos) (what a cache recomputation replays)
+  bool hist_known = true;      // false for sequences admitted mid-life without their history
   int32_t n_prompt = 0, max_new = 0, pos = 0, n_emitted = 0, next_input = -1;
   float inv_t = 1.f;
   std::vector<int32_t> pages;
@@ -78,7 +80,7 @@ struct pl_engine {
   int active_buf = 0;
   uint32_t version = 0;
   bool loaded = false;
-  bool staged = false, staged_wait = false;
+  bool staged = false, staged_wait = false, staged_recompute = false;
   uint32_t staged_version = 0;
   hipEvent_t ev_staged = nullptr, ev_copy0 = nullptr;
   // kv
@@ -359,6 +361,7 @@ int admit(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt
   q.max_new = max_new;
   q.inv_t = 1.0f / temp;
   q.pos = context_len;
+  q.hist_known = context_len == 0;
   q.n_emitted = n_emitted;
   q.next_input = last_token;
   for (int64_t i = 0; i < need_pages; ++i) {
@@ -368,6 +371,75 @@ int admit(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt
   }
   e->pt_dirty = true;
   if (out_slot) *out_slot = slot;
+  return PL_OK;
+}
+
+// Cache-only passes: rows (slot, position, token) go through the decode kernels in prefill mode, in
+// groups of up to min(max_batch, 256); the rows of one slot must come in position order, because a
+// row attends to the keys and values that earlier rows of its slot (in this or an earlier group) leave.
+int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::vector<int32_t> &positions,
+                  const std::vector<int32_t> &tokens, double *ms_total, uint64_t *passes) {
+  const pl_model_cfg &c = e->cfg;
+  const int rows_max = std::min<int>(c.max_batch, 256);
+  int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
+  float *inv_t = e->m_inv_t(false);
+  uint64_t *sid = e->m_seq_id(false);
+  if (!e->dry) HIP_TRY(hipSetDevice(c.device));
+  const size_t total = slots.size();
+  for (size_t r0 = 0; r0 < total; r0 += rows_max) {
+    const int n = (int)std::min<size_t>(rows_max, total - r0);
+    int items = 0;
+    for (int r = 0; r < n; ++r) {
+      const Seq &q = e->seqs[slots[r0 + r]];
+      row_slot[r] = slots[r0 + r];
+      pos[r] = positions[r0 + r];
+      inp[r] = tokens[r0 + r];
+      frc[r] = -1;
+      inv_t[r] = q.inv_t;
+      sid[r] = q.seq_id;
+      items += (pos[r] + 1 + e->attn_chunk - 1) / e->attn_chunk;
+    }
+    e->attn_items = items;
+    if (!e->dry) {
+      hipStream_t s = e->s_dec;
+      if (e->pt_dirty) {
+        HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
+        e->pt_dirty = false;
+      }
+      HIP_TRY(hipMemcpyAsync(e->meta_d, e->meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
+      HIP_TRY(hipEventRecord(e->ev_a, s));
+      const int prof = e->profile;
+      e->profile = 0;   // the per-group timers describe decode steps only
+      int rc = enqueue_step(e, n, true);
+      e->profile = prof;
+      if (rc) return rc;
+      HIP_TRY(hipEventRecord(e->ev_b, s));
+      HIP_TRY(hipStreamSynchronize(s));   // the host metadata image is reused by the next group
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, e->ev_a, e->ev_b));
+      *ms_total += ms;
+    }
+    ++*passes;
+  }
+  return PL_OK;
+}
+
+// "KV cache recomputed" variant of Sec. 5.1: after a flip, replay every token each sequence has read
+// so far under the new weights, overwriting its cached keys and values in place.
+int recompute_all_kv(pl_engine *e) {
+  std::vector<int32_t> slots, positions, tokens;
+  for (int s = 0; s < e->cfg.max_batch; ++s) {
+    const Seq &q = e->seqs[s];
+    if (!q.active) continue;
+    for (int p = 0; p < q.pos; ++p) {
+      slots.push_back(s);
+      positions.push_back(p);
+      tokens.push_back(q.hist[p]);
+    }
+  }
+  int rc = run_kv_passes(e, slots, positions, tokens, &e->st.recompute_ms, &e->st.recompute_passes);
+  if (rc) return rc;
+  e->st.recompute_positions += slots.size();
   return PL_OK;
 }
 
@@ -470,12 +542,16 @@ int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes) {
 
 int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flags, uint32_t *out_new_version) {
   if (!e || !src) return fail(PL_E_INVAL, "NULL argument");
-  if (flags != PL_SWAP_ASYNC && flags != PL_SWAP_WAIT) return fail(PL_E_INVAL, "unknown flags");
+  if (flags & ~(PL_SWAP_WAIT | PL_SWAP_RECOMPUTE_KV)) return fail(PL_E_INVAL, "unknown flags");
+  if (flags & PL_SWAP_RECOMPUTE_KV)
+    for (const Seq &q : e->seqs)
+      if (q.active && !q.hist_known) return fail(PL_E_STATE, "a sequence was admitted without its token history; its cache cannot be recomputed");
   if (nbytes != e->blob_elems * 2) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * 2));
   if (!e->loaded) return fail(PL_E_STATE, "no weights loaded yet");
   if (e->staged) return fail(PL_E_BUSY, "the previous weight update is not active yet");
   e->staged_version = e->version + 1;
-  e->staged_wait = (flags == PL_SWAP_WAIT);
+  e->staged_wait = (flags & PL_SWAP_WAIT) != 0;
+  e->staged_recompute = (flags & PL_SWAP_RECOMPUTE_KV) != 0;
   if (!e->dry) {
     HIP_TRY(hipSetDevice(e->cfg.device));
     if (e->cfg.n_weight_buffers == 2) {
@@ -523,6 +599,18 @@ int pl_debug_add_sequence_at(pl_engine *e, uint64_t seq_id, const int32_t *promp
                              int32_t *out_slot) {
   if (!e) return fail(PL_E_INVAL, "NULL argument");
   return admit(e, seq_id, prompt, n_prompt, max_new, temperature, context_len, n_emitted, last_token, out_slot);
+}
+
+int pl_debug_set_history(pl_engine *e, int32_t slot, const int32_t *tokens, int32_t n) {
+  if (!e || !tokens) return fail(PL_E_INVAL, "NULL argument");
+  if (slot < 0 || slot >= e->cfg.max_batch || !e->seqs[slot].active) return fail(PL_E_STATE, "slot %d is idle", slot);
+  Seq &q = e->seqs[slot];
+  if (n != q.pos) return fail(PL_E_INVAL, "history must cover the %d positions read so far", q.pos);
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= e->cfg.vocab) return fail(PL_E_INVAL, "token %d out of range", tokens[i]);
+  q.hist.assign(tokens, tokens + n);
+  q.hist_known = true;
+  return PL_OK;
 }
 
 int pl_retire_sequence(pl_engine *e, int32_t slot) {
@@ -583,6 +671,17 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, e->ev_copy0, e->ev_staged) == hipSuccess) e->st.last_swap_copy_ms = ms;
       (void)hipGetLastError();
+    }
+    if (!e->staged && e->staged_recompute) {
+      // the update asked for the caches to be rebuilt under the new weights: do it now, before the
+      // first token is produced from them; the time counts as this step's stall
+      e->staged_recompute = false;
+      if (!e->dry && !timed_stall) {
+        HIP_TRY(hipEventRecord(e->ev_c, e->s_dec));
+        timed_stall = true;
+      }
+      int rc = recompute_all_kv(e);
+      if (rc) return rc;
     }
   }
 
@@ -669,6 +768,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     if (out->position) out->position[r] = q.pos;
     if (out->emitted) out->emitted[r] = emitted;
     if (out->finished) out->finished[r] = fin;
+    if (q.hist_known) q.hist.push_back(inp[r]);
     q.pos++;
     ++r;
   }
@@ -691,46 +791,12 @@ int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
   if (first >= last) return PL_OK;
   if ((int)q.prompt.size() < q.n_prompt) return fail(PL_E_STATE, "slot %d holds no prompt", slot);
   if ((int64_t)q.pages.size() * e->page_tokens < last) return fail(PL_E_STATE, "slot %d has no pages for its prompt", slot);
-  const int rows_max = std::min<int>(c.max_batch, 256);
-  int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
-  float *inv_t = e->m_inv_t(false);
-  uint64_t *sid = e->m_seq_id(false);
-  if (!e->dry) HIP_TRY(hipSetDevice(c.device));
-  for (int p0 = first; p0 < last; p0 += rows_max) {
-    const int n = std::min(rows_max, last - p0);
-    int items = 0;
-    for (int r = 0; r < n; ++r) {
-      row_slot[r] = slot;
-      pos[r] = p0 + r;
-      inp[r] = q.prompt[p0 + r];
-      frc[r] = -1;
-      inv_t[r] = q.inv_t;
-      sid[r] = q.seq_id;
-      items += (p0 + r + 1 + e->attn_chunk - 1) / e->attn_chunk;
-    }
-    e->attn_items = items;
-    if (!e->dry) {
-      hipStream_t s = e->s_dec;
-      if (e->pt_dirty) {
-        HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
-        e->pt_dirty = false;
-      }
-      HIP_TRY(hipMemcpyAsync(e->meta_d, e->meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
-      HIP_TRY(hipEventRecord(e->ev_a, s));
-      const int prof = e->profile;
-      e->profile = 0;   // the per-group timers describe decode steps only
-      int rc = enqueue_step(e, n, true);
-      e->profile = prof;
-      if (rc) return rc;
-      HIP_TRY(hipEventRecord(e->ev_b, s));
-      HIP_TRY(hipStreamSynchronize(s));   // the host metadata image is reused by the next pass
-      float ms = 0.f;
-      HIP_TRY(hipEventElapsedTime(&ms, e->ev_a, e->ev_b));
-      e->st.prefill_ms += ms;
-    }
-    e->st.prefill_passes++;
-    e->st.prefill_positions += n;
-  }
+  std::vector<int32_t> slots(last - first, slot), positions, tokens;
+  for (int p = first; p < last; ++p) { positions.push_back(p); tokens.push_back(q.prompt[p]); }
+  int rc = run_kv_passes(e, slots, positions, tokens, &e->st.prefill_ms, &e->st.prefill_passes);
+  if (rc) return rc;
+  e->st.prefill_positions += last - first;
+  if (q.hist_known) q.hist.insert(q.hist.end(), tokens.begin(), tokens.end());
   q.pos = last;
   e->last_n = 0;
   if (out_positions) *out_positions = last - first;

@@ -223,3 +223,28 @@ def test_batched_prefill_bookkeeping():
     r = e.decode_step()
     i = r["slot"].tolist().index(s2)
     assert r["position"][i] == 9 and r["emitted"][i] == 1
+
+
+def test_cache_recomputation_bookkeeping():
+    e = _loaded()
+    s0 = e.add_sequence(1, [5, 6, 7], 10)
+    for _ in range(4):
+        e.decode_step()
+    blob = np.zeros(e.weight_nbytes() // 2, np.uint16)
+    e.swap_weights(blob, flags=pl.PL_SWAP_ASYNC | pl.PL_SWAP_RECOMPUTE_KV)
+    assert e.stats()["recompute_positions"] == 0                 # nothing happens before the step boundary
+    r = e.decode_step()
+    assert r["weight_version"][0] == 1 and e.stats()["recompute_positions"] == 4
+    s1 = e.debug_add_sequence_at(9, None, 16, 64, 1.0, context_len=20, n_emitted=5, last_token=3)
+    with pytest.raises(pl.PlError) as ex:                        # no history for the slot admitted mid-life
+        e.swap_weights(blob, flags=pl.PL_SWAP_WAIT | pl.PL_SWAP_RECOMPUTE_KV)
+    assert ex.value.code == pl.PL_E_STATE
+    with pytest.raises(pl.PlError):
+        e.debug_set_history(s1, np.arange(19))                   # must cover exactly the 20 positions read
+    e.debug_set_history(s1, np.arange(20))
+    e.swap_weights(blob, flags=pl.PL_SWAP_WAIT | pl.PL_SWAP_RECOMPUTE_KV)
+    e.decode_step()
+    assert e.stats()["recompute_positions"] == 4 + 5 + 20
+    with pytest.raises(pl.PlError) as ex:
+        e.swap_weights(blob, flags=8)
+    assert ex.value.code == pl.PL_E_INVAL

@@ -36,7 +36,7 @@ def _engine(max_batch=4, **kw):
     return pl.Engine.from_model(M, **args)
 
 
-def _teacher_forced(weights, swap_steps, n_prompt=16, max_new=64, batch=4, n_weight_buffers=2):
+def _teacher_forced(weights, swap_steps, n_prompt=16, max_new=64, batch=4, n_weight_buffers=2, recompute=False):
     master, pert = weights
     versions = [master, pert]
     eng = _engine(batch, n_weight_buffers=n_weight_buffers)
@@ -51,8 +51,9 @@ def _teacher_forced(weights, swap_steps, n_prompt=16, max_new=64, batch=4, n_wei
     for step in range(n_prompt + max_new - 1):
         if step in swap_steps:
             cur ^= 1
-            orc.swap_weights(_rounded(versions[cur]))
-            assert eng.swap_weights(blobs[cur], flags=pl.PL_SWAP_WAIT) == orc.version
+            orc.swap_weights(_rounded(versions[cur]), recompute_kv=recompute)
+            flags = pl.PL_SWAP_WAIT | (pl.PL_SWAP_RECOMPUTE_KV if recompute else 0)
+            assert eng.swap_weights(blobs[cur], flags=flags) == orc.version
         recs = orc.decode_step()
         forced = np.full(batch, -1, np.int32)
         for r in recs:
@@ -346,3 +347,56 @@ def test_batched_prefill_under_the_weights_active_at_admission_then_a_swap(weigh
     for _ in range(6):
         both_step()
     eng.close()
+
+
+# ---- "KV cache recomputed" variant of the in-flight update (Sec. 5.1) -------------------------------
+
+def test_swap_with_cache_recomputation_matches_the_oracle(weights):
+    _teacher_forced(weights, swap_steps={20, 47}, recompute=True)
+    _teacher_forced(weights, swap_steps={30}, max_new=24, n_weight_buffers=1, recompute=True)
+
+
+def test_recomputed_cache_equals_the_cache_of_a_run_under_the_new_weights_from_the_start(weights):
+    """What is unique: replaying the tokens under W' must leave, bit for bit, the cache an engine holds
+    that read the same tokens under W' all along; with W' = W the cache must not change at all."""
+    master, pert = weights
+    prompts = synth.random_prompts(np.random.default_rng(21), 3, 9, M.vocab)
+    eng_a, eng_b = _engine(), _engine()
+    blobs = [eng_a.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
+    eng_a.load_weights(blobs[0])
+    eng_b.load_weights(blobs[1])
+    for i in range(3):
+        eng_a.add_sequence(70 + i, prompts[i], 40)
+        eng_b.add_sequence(70 + i, prompts[i], 40)
+    eng_a.prefill(0)                                             # one slot reads its prompt in a batched pass
+    eng_b.prefill(0)
+    for step in range(8):
+        out = eng_a.decode_step()                                # slot 0 is already generating
+        forced = np.full(4, -1, np.int32)
+        forced[out["slot"]] = out["token"]
+        eng_b.decode_step(forced)
+    before = [_kv_of(eng_a, i, 8 if i else 16) for i in range(3)]
+    eng_a.swap_weights(blobs[0], flags=pl.PL_SWAP_WAIT | pl.PL_SWAP_RECOMPUTE_KV)     # W' = W
+    out = eng_a.decode_step()
+    assert out["swap_stall_ms"] > 0 and eng_a.stats()["recompute_positions"] == 16 + 8 + 8
+    forced = np.full(4, -1, np.int32)
+    forced[out["slot"]] = out["token"]
+    eng_b.decode_step(forced)
+    for i in range(3):
+        after = _kv_of(eng_a, i, 8 if i else 16)
+        for l in range(M.n_layers):
+            assert np.array_equal(before[i][l][0], after[l][0]) and np.array_equal(before[i][l][1], after[l][1])
+    eng_a.swap_weights(blobs[1], flags=pl.PL_SWAP_WAIT | pl.PL_SWAP_RECOMPUTE_KV)     # now the new weights
+    for step in range(4):
+        out = eng_a.decode_step()
+        forced = np.full(4, -1, np.int32)
+        forced[out["slot"]] = out["token"]
+        ob = eng_b.decode_step(forced)
+        assert np.array_equal(eng_a.debug_get_logits(3), eng_b.debug_get_logits(3)), step
+        assert np.array_equal(out["logprob"], ob["logprob"])
+    for i in range(3):
+        n = (9 if i else 17) + 4
+        ka, kb = _kv_of(eng_a, i, n), _kv_of(eng_b, i, n)
+        for l in range(M.n_layers):
+            assert np.array_equal(ka[l][0], kb[l][0]) and np.array_equal(ka[l][1], kb[l][1]), (i, l)
+    eng_a.close(); eng_b.close()
