@@ -189,8 +189,90 @@ def cpu_baseline(model, seconds_budget=20.0):
                       f"extrapolated to {model.n_layers} layers (one step = {per_token:.3f} s per sequence)"}
 
 
+def batch_study(args):
+    """Throughput against the number of sequences in flight (the shape of Fig. 2a), and the replay of a
+    generation stage that is not refilled (Fig. 2b/2c: the batch decays as sequences finish).  Both use
+    the workload's model shape and length law; prints one JSON line of its own."""
+    import torch
+    import paper_2509_19128_amd as pl
+
+    spec = WORKLOADS[args.workload]
+    model = synth.CONFIGS[spec["model"]]
+    P, max_ctx = spec["prompt"], spec["prompt"] + spec["gmax"]
+    rng = np.random.default_rng(4321)
+    blob = None
+    per_tok = 2 * model.n_layers * model.n_kv_heads * model.head_dim * 2
+
+    def timed(B, contexts, steps=24, warmup=4):
+        """tokens/s of decode steps for sequences at the given context lengths in an engine sized for B."""
+        nonlocal blob
+        ctxs = np.minimum(np.asarray(contexts, np.int64), max_ctx - steps - warmup - 2)
+        pool = int(sum((int(c) + steps + warmup + 256) for c in ctxs)) + 1024
+        eng = pl.Engine.from_model(model, max_batch=B, max_context=max_ctx, kv_pool_tokens=pool,
+                                   n_weight_buffers=1, seed=99, device=0)
+        if blob is None:
+            blob = device_weight_blob(eng, torch, seed=1237)
+            torch.cuda.synchronize()
+        eng.load_weights(blob.data_ptr(), eng.weight_nbytes())
+        fill_kv_pool(eng, torch, seed=7)
+        for i, c in enumerate(ctxs):
+            c = int(max(c, P - 1))
+            eng.debug_add_sequence_at(i, rng.integers(0, model.vocab, P), P, max_ctx - P, 1.0, c, c - (P - 1),
+                                      int(rng.integers(model.vocab)))
+        for _ in range(warmup):
+            eng.decode_step()
+        s0 = eng.stats()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            eng.decode_step()
+        wall = time.perf_counter() - t0
+        s1 = eng.stats()
+        eng.close()
+        toks = s1["tokens_emitted"] - s0["tokens_emitted"]
+        return {"tokens_per_s": toks / wall, "ms_per_step": 1e3 * wall / steps,
+                "gpu_ms_per_step": (s1["gpu_ms_total"] - s0["gpu_ms_total"]) / steps,
+                "mean_context": float(np.mean(ctxs)), "hbm_GBs": (s1["algorithmic_bytes"] - s0["algorithmic_bytes"]) / wall / 1e9}
+
+    # stationary context mix of the refilled batch (prompts already read): generation length drawn
+    # length-biased, age uniform
+    cand = synth.lognormal_lengths(rng, 200_000, spec["mean"], 1, spec["gmax"])
+    sweep = []
+    for B in [1, 2, 4, 8, 16, 32, 64, 128, 192, 256, 384, 512]:
+        g = rng.choice(cand, size=B, p=cand / cand.sum())
+        ctx = P - 1 + (rng.random(B) * g).astype(np.int64)
+        r = timed(B, ctx)
+        r["batch"] = B
+        sweep.append(r)
+        print(f"# batch {B}: {r['tokens_per_s']:.0f} tokens/s, {r['ms_per_step']:.2f} ms/step", file=sys.stderr, flush=True)
+    # a stage that is not refilled: B sequences start together; after t steps those with length > t
+    # are alive, all at context P - 1 + t
+    B0 = spec["batch"]
+    lens = synth.lognormal_lengths(rng, B0, spec["mean"], 1, spec["gmax"])
+    decay, t = [], 0
+    while True:
+        alive = int((lens > t).sum())
+        if alive == 0:
+            break
+        r = timed(B0, [P - 1 + t] * alive, steps=12, warmup=2)
+        r.update(step=t, alive=alive)
+        decay.append(r)
+        print(f"# step {t}: {alive} alive, {r['tokens_per_s']:.0f} tokens/s", file=sys.stderr, flush=True)
+        t += 1024
+    total_tokens = int(lens.sum())
+    # time of the whole stage from the sampled step times (trapezoid over the sampled points)
+    ts = [d["step"] for d in decay] + [int(lens.max())]
+    ms = [d["ms_per_step"] for d in decay] + [decay[-1]["ms_per_step"]]
+    stage_s = sum(0.5 * (ms[i] + ms[i + 1]) * (ts[i + 1] - ts[i]) for i in range(len(ts) - 1)) / 1e3
+    print(json.dumps({"study": "throughput against sequences in flight, and a generation stage without refill",
+                      "workload": args.workload, "sweep": sweep, "decay": decay,
+                      "decay_stage": {"sequences": B0, "tokens": total_tokens, "seconds": stage_s,
+                                      "tokens_per_s": total_tokens / stage_s}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--batch-study", action="store_true",
+                    help="instead of the benchmark line: throughput against batch size and a replay of a stage without refill")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
@@ -208,6 +290,9 @@ def main():
         print("bench.py measures one engine replica on one GPU; data-parallel replicas are independent "
               "and are not launched here (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
+
+    if args.batch_study:
+        return batch_study(args)
 
     import torch
     import paper_2509_19128_amd as pl
