@@ -269,8 +269,58 @@ def batch_study(args):
                                       "tokens_per_s": total_tokens / stage_s}}))
 
 
+def is_ess_study(args):
+    """The trainer-side reduction over one optimizer batch of recorded log-probs (Sec. 2.1): 1024 packed
+    sequences with the workload's generation lengths; prints one JSON line of its own."""
+    import torch
+    import paper_2509_19128_amd as pl
+    from oracle import importance
+
+    spec = WORKLOADS["7b"]
+    rng = np.random.default_rng(77)
+    lens = synth.lognormal_lengths(rng, 1024, spec["mean"], 1, spec["gmax"])
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    n = int(off[-1])
+    mu = (-rng.random(n) * 6).astype(np.float32)
+    pi = (mu + rng.normal(0, 0.3, n)).astype(np.float32)
+    d_pi, d_mu, d_off = (torch.from_numpy(x).cuda() for x in (pi, mu, off))
+    w = torch.empty(n, device="cuda", dtype=torch.float32)
+    sums = torch.empty((1024, 2), device="cuda", dtype=torch.float64)
+    ess = torch.empty(1024, device="cuda", dtype=torch.float64)
+    tot = torch.empty(3, device="cuda", dtype=torch.float64)
+    s = torch.cuda.current_stream()
+    call = lambda: pl.pl_is_ess(d_pi.data_ptr(), d_mu.data_ptr(), d_off.data_ptr(), 1024, 5.0, w.data_ptr(),
+                                sums.data_ptr(), ess.data_ptr(), tot.data_ptr(), s.cuda_stream)
+    for _ in range(args.warmup):
+        call()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(s)
+    for _ in range(args.steps):
+        call()
+    b.record(s)
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / args.steps
+    nbytes = 12.0 * n + 8 * 1025 + 24 * 1024                      # 2 reads + 1 write per token, offsets, per-sequence outputs
+    m = min(n, 400_000)                                           # oracle on a bounded sample of the same batch
+    k = int(np.searchsorted(off, m, side="right")) - 1
+    t0 = time.perf_counter()
+    _, _, et = importance.packed_is_ess(pi[:off[k]], mu[:off[k]], off[:k + 1], 5.0)
+    t_cpu = time.perf_counter() - t0
+    print(json.dumps({"metric": "tokens/s through the truncated-importance-weight + ESS reduction", "value": n / (ms * 1e-3),
+                      "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "dtype": "f64", "data": "synthetic",
+                      "config": {"workload": "1024 packed sequences, lognormal(4096, 0.75, max 16384) lengths", "tokens": n},
+                      "ess_total": float(tot.cpu()[2]),
+                      "roofline": {"bound": "hbm", "kernel": "is_seq_kernel (+ is_total_kernel)", "achieved": nbytes / (ms * 1e-3) / 1e9,
+                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+                      "cpu_baseline": {"value": int(off[k]) / t_cpu, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                       "sample": f"first {k} sequences ({int(off[k])} tokens) of the same batch"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--is-ess", action="store_true",
+                    help="instead of the benchmark line: time the importance-weight / ESS reduction on one optimizer batch")
     ap.add_argument("--batch-study", action="store_true",
                     help="instead of the benchmark line: throughput against batch size and a replay of a stage without refill")
     ap.add_argument("--gpus", type=int, default=1)
@@ -293,6 +343,8 @@ def main():
 
     if args.batch_study:
         return batch_study(args)
+    if args.is_ess:
+        return is_ess_study(args)
 
     import torch
     import paper_2509_19128_amd as pl

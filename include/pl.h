@@ -272,6 +272,22 @@ int pl_sample(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq
               const int32_t *position, const float *inv_temperature, const int32_t *forced,
               uint64_t seed, int32_t *token, float *logprob, void *workspace, void *stream);
 
+/* Trainer-side use of the recorded log-probs (Sec. 2.1): truncated token-level importance weights
+ * w_i = min(c, exp(logp_pi[i] - logp_mu[i])) (the paper clamps at c = 5) and the normalised effective
+ * sample size (sum w)^2 / (N sum w^2) (Sec. 2.1, ESS), per sequence of a packed batch and over all its
+ * tokens.  All device pointers:
+ *   logp_pi, logp_mu  fp32 [n_tokens]: log-prob of each token under the current policy and the
+ *                     behaviour log-prob the engine recorded for it
+ *   seq_offsets       int64 [n_seq + 1], non-decreasing: sequence s owns tokens [off[s], off[s+1])
+ *   w_out             fp32 [n_tokens] or NULL
+ *   seq_sums          fp64 [n_seq, 2]: sum w and sum w^2 of each sequence
+ *   ess_seq           fp64 [n_seq]: normalised ESS of each sequence (NaN for an empty one)
+ *   totals            fp64 [3]: sum w, sum w^2 and normalised ESS over all tokens
+ * fp64 arithmetic, fixed reduction order (bit-reproducible).  PL_E_INVAL for c <= 0 or n_seq < 1.
+ * Asynchronous on `stream`; the caller owns every buffer. */
+int pl_is_ess(const float *logp_pi, const float *logp_mu, const int64_t *seq_offsets, int32_t n_seq, float c,
+              float *w_out, double *seq_sums, double *ess_seq, double *totals, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

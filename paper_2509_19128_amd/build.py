@@ -17,7 +17,8 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the sampler's float32 decision must not be re-associated or fused
 PER_FILE = {"kernels_sample.hip": ["-ffp-contract=off"]}
-SOURCES = ["pl_engine.hip", "kernels_attn.hip", "kernels_gemm.hip", "kernels_misc.hip", "kernels_sample.hip"]
+SOURCES = ["pl_engine.hip", "kernels_attn.hip", "kernels_gemm.hip", "kernels_misc.hip", "kernels_sample.hip",
+           "kernels_is.hip"]
 
 
 def _run(cmd):
@@ -37,7 +38,7 @@ def build(verbose: bool = False) -> str:
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
         objs.append(obj)
         jobs.append([HIPCC, *COMMON, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
-    with ThreadPoolExecutor(max_workers=min(5, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
         list(ex.map(_run, jobs))
     _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs])
     if verbose:

@@ -72,5 +72,7 @@ int launch_rope_append(const float *qkv, int splits, const float *cs, const int3
                        int n, int Hq, int Hkv, int hd, int page_tokens, int pages_per_seq, hipStream_t s);
 int64_t launch_stream_read(const void *p, int64_t nbytes, uint32_t *sink, hipStream_t s);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);
+int launch_is_ess(const float *lp_pi, const float *lp_mu, const int64_t *offsets, int n_seq, double c, float *w_out,
+                  double *seq_sums, double *ess_seq, double *totals, hipStream_t s);
 
 }  // namespace pl

@@ -916,6 +916,16 @@ int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page
   return PL_OK;
 }
 
+int pl_is_ess(const float *logp_pi, const float *logp_mu, const int64_t *seq_offsets, int32_t n_seq, float c,
+              float *w_out, double *seq_sums, double *ess_seq, double *totals, void *stream) {
+  if (!logp_pi || !logp_mu || !seq_offsets || !seq_sums || !ess_seq || !totals) return fail(PL_E_INVAL, "NULL argument");
+  if (n_seq < 1) return fail(PL_E_INVAL, "n_seq must be positive");
+  if (!(c > 0.f)) return fail(PL_E_INVAL, "the truncation level c must be positive");
+  if (pl::launch_is_ess(logp_pi, logp_mu, seq_offsets, n_seq, (double)c, w_out, seq_sums, ess_seq, totals, (hipStream_t)stream))
+    return fail(PL_E_HIP, "importance-weight launch failed");
+  return PL_OK;
+}
+
 int pl_kv_pack_host(uint16_t *pages_host, const int32_t *page_ids, const float *k, const float *v, int32_t first_pos,
                     int32_t n, int32_t n_kv_heads, int32_t hd, int32_t page_tokens) {
   if (!pages_host || !page_ids || !k || !v) return fail(PL_E_INVAL, "NULL argument");
