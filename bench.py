@@ -128,9 +128,9 @@ class Workload:
         return emitted, out["step_ms"], out["swap_stall_ms"], out["weight_version"][0] if out["n"] else 0
 
 
-def stream_ceiling(torch, pl):
-    """Read bandwidth HBM delivers to a kernel that only reads (GB/s), timed with events on torch's
-    current stream, where the probe is launched."""
+def stream_ceiling(torch, pl, nontemporal=False):
+    """Read bandwidth HBM delivers to a kernel that only reads (GB/s; ordinary or non-temporal loads),
+    timed with events on torch's current stream, where the probe is launched."""
     buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
     buf.random_(0, 255)
     best = 0.0
@@ -138,7 +138,7 @@ def stream_ceiling(torch, pl):
     for _ in range(5):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(s)
-        n = pl.pl_debug_stream_read(buf.data_ptr(), buf.numel(), s.cuda_stream)
+        n = pl.pl_debug_stream_read(buf.data_ptr(), buf.numel(), nontemporal, s.cuda_stream)
         b.record(s)
         torch.cuda.synchronize()
         best = max(best, n / (a.elapsed_time(b) * 1e-3) / 1e9)
@@ -446,6 +446,7 @@ def main():
                     "passes": s1["prefill_passes"] - s0["prefill_passes"], "gpu_ms": s1["prefill_ms"] - s0["prefill_ms"]},
     }
     res["hbm_read_stream_ceiling_GBs"] = stream_ceiling(torch, pl)
+    res["hbm_read_stream_ceiling_nontemporal_GBs"] = stream_ceiling(torch, pl, nontemporal=True)
     if d["attn_launches"]:
         per_launch_bytes = d["attn_kv_bytes"] / d["attn_launches"]
         per_launch_ms = d["attn_ms"] / d["attn_launches"]

@@ -217,10 +217,10 @@ int pl_debug_set_profile(pl_engine *e, int32_t level);
 /* Device pointer and size of the KV page pool (to fill it with synthetic values). */
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 
-/* Launch a kernel that only reads the device buffer (contiguous 16-byte loads, 8 in flight per lane)
- * on `stream`; returns the number of bytes it reads (a multiple of 256 MiB, <= nbytes) or a negative
+/* Launch a kernel that only reads the device buffer (contiguous 16-byte loads, 8 in flight per lane;
+ * ordinary loads, or non-temporal ones if `nontemporal` is non-zero) on `stream`; returns the number of bytes it reads (a multiple of 256 MiB, <= nbytes) or a negative
  * pl_status.  Timed by the caller, it gives the read bandwidth HBM delivers on this board. */
-int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, void *stream);
+int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, int32_t nontemporal, void *stream);
 
 /* ---- kernel-level entry points (device pointers; `stream` is a hipStream_t or NULL) ----------- */
 

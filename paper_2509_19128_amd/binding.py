@@ -102,7 +102,7 @@ def lib():
         "pl_debug_add_sequence_at": (C.c_int, [vp, u64, vp, i32, i32, f32, i32, i32, i32, P(i32)]),
         "pl_debug_kv_pool": (C.c_int, [vp, P(vp), P(i64)]),
         "pl_debug_set_profile": (C.c_int, [vp, i32]),
-        "pl_debug_stream_read": (i64, [vp, i64, vp]),
+        "pl_debug_stream_read": (i64, [vp, i64, i32, vp]),
         "pl_attention_workspace_bytes": (i64, [i32, i32, i32, i32, i32]),
         "pl_attention_decode": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "pl_kv_pack_host": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32]),
@@ -348,8 +348,8 @@ def pl_kv_pack_host(pages_host, page_ids, k, v, first_pos, n_kv_heads, hd, page_
                                  k.shape[0], n_kv_heads, hd, page_tokens))
 
 
-def pl_debug_stream_read(ptr, nbytes, stream=0):
-    r = int(lib().pl_debug_stream_read(ptr, nbytes, stream))
+def pl_debug_stream_read(ptr, nbytes, nontemporal=False, stream=0):
+    r = int(lib().pl_debug_stream_read(ptr, nbytes, int(bool(nontemporal)), stream))
     if r < 0:
         raise PlError(r, lib().pl_last_error().decode())
     return r

@@ -217,23 +217,28 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
   if (b == 0) work[0] = total_full + sc[1023];
 }
 
+// Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup per (sequence, kv
+// head); most sequences fit one chunk and their workgroups leave at once.
 template <int HD>
-__global__ __launch_bounds__(HD) void attn_combine_kernel(AttnParams p) {
-  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
+  const int b = blockIdx.y, g = blockIdx.x;
   const int ctx = p.ctx_len[b];
   if (ctx <= p.chunk) return;   // empty rows and single-chunk rows were written by the first kernel
-  const int G = p.Hq / p.Hkv, g = hq / G, h = hq % G;
+  const int G = p.Hq / p.Hkv;
   const int nchunk = (ctx + p.chunk - 1) / p.chunk;
   const int64_t base = ((int64_t)b * p.Hkv + g) * p.max_chunks;
-  float M = -INFINITY;
-  for (int c = 0; c < nchunk; ++c) M = fmaxf(M, p.part_ml[((base + c) * G + h) * 2]);
-  float L = 0.f, O = 0.f;
-  for (int c = 0; c < nchunk; ++c) {
-    float f = __builtin_amdgcn_exp2f(p.part_ml[((base + c) * G + h) * 2] - M);
-    L += p.part_ml[((base + c) * G + h) * 2 + 1] * f;
-    O += p.part_o[((base + c) * G + h) * HD + d] * f;
+  for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
+    const int h = idx / HD, d = idx % HD;
+    float M = -INFINITY;
+    for (int c = 0; c < nchunk; ++c) M = fmaxf(M, p.part_ml[((base + c) * G + h) * 2]);
+    float L = 0.f, O = 0.f;
+    for (int c = 0; c < nchunk; ++c) {
+      float f = __builtin_amdgcn_exp2f(p.part_ml[((base + c) * G + h) * 2] - M);
+      L += p.part_ml[((base + c) * G + h) * 2 + 1] * f;
+      O += p.part_o[((base + c) * G + h) * HD + d] * f;
+    }
+    p.out[((int64_t)b * p.Hq + g * G + h) * HD + d] = (__bf16)(O / L);
   }
-  p.out[((int64_t)b * p.Hq + hq) * HD + d] = (__bf16)(O / L);
 }
 
 }  // namespace
@@ -258,19 +263,19 @@ int launch_attention_worklist(const int32_t *ctx_len, int32_t *work, int n_seq, 
 int launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_seq <= 0) return 0;
   // max_items bounds the list (the host knows the longest context of the step, or uses max_chunks)
-  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hq, p.n_seq);
+  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hkv, p.n_seq);
   switch (p.hd) {
     case 128:
       hipLaunchKernelGGL((attn_decode_kernel<128, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(128), 0, s, p);
+      hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(256), 0, s, p);
       break;
     case 64:
       hipLaunchKernelGGL((attn_decode_kernel<64, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p);
+      hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(256), 0, s, p);
       break;
     case 32:
       hipLaunchKernelGGL((attn_decode_kernel<32, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(32), 0, s, p);
+      hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(256), 0, s, p);
       break;
     default:
       return -1;

@@ -956,9 +956,9 @@ int pl_gemm_bf16(const void *x, const void *w, void *y, int32_t M, int32_t N, in
   return PL_OK;
 }
 
-int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, void *stream) {
+int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, int32_t nontemporal, void *stream) {
   if (!device_ptr || nbytes < (int64_t)16 * 8192 * 2048) return fail(PL_E_INVAL, "need a device buffer of at least 256 MiB");
-  int64_t r = pl::launch_stream_read(device_ptr, nbytes, nullptr, (hipStream_t)stream);
+  int64_t r = pl::launch_stream_read(device_ptr, nbytes, nullptr, nontemporal != 0, (hipStream_t)stream);
   if (r < 0) return fail(PL_E_HIP, "stream read launch failed");
   return r;
 }
