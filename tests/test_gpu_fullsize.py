@@ -54,15 +54,16 @@ class _LazyWeights(dict):
         return self.cur[name]
 
 
-def test_7b_bench_configuration_sampled_rows_against_oracle():
+@pytest.fixture(scope="module")
+def full():
+    """The engine exactly as bench.py sets it up, plus a host copy of its weight blob."""
     import torch
     import bench
 
     spec = dict(bench.WORKLOADS["7b"], pool_tokens=1_300_000)
     m = synth.CONFIGS["7b"]
-    B = spec["batch"]
     seed = 1234 + 3
-    eng = pl.Engine.from_model(m, max_batch=B, max_context=spec["prompt"] + spec["gmax"],
+    eng = pl.Engine.from_model(m, max_batch=spec["batch"], max_context=spec["prompt"] + spec["gmax"],
                                kv_pool_tokens=spec["pool_tokens"], n_weight_buffers=2, seed=seed, device=0)
     blob_d = bench.device_weight_blob(eng, torch, seed=1237)
     torch.cuda.synchronize()
@@ -73,6 +74,13 @@ def test_7b_bench_configuration_sampled_rows_against_oracle():
     bench.fill_kv_pool(eng, torch, seed=1239)
     wl = bench.Workload(eng, spec, m, seed=seed)
     wl.admit_steady_state()
+    yield eng, blob, m, spec, seed
+    eng.close()
+
+
+def test_7b_bench_configuration_sampled_rows_against_oracle(full):
+    eng, blob, m, spec, seed = full
+    B = spec["batch"]
 
     first = eng.decode_step()
     n = first["n"]
@@ -123,4 +131,45 @@ def test_7b_bench_configuration_sampled_rows_against_oracle():
         scale = max(1.0, float(ref.std()) / 0.32) * np.sqrt(m.n_layers)
         assert close(logits[r], ref, 2e-2 * scale, 1e-2)[0], r
         assert int(np.argmax(logits[r])) in np.argsort(ref)[-5:]
-    eng.close()
+
+
+def test_7b_batched_prompt_reading_at_full_size(full):
+    """pl_prefill in the benchmark's configuration.  Unique result: the cache it leaves is bit-identical
+    to the one the same prompt leaves when read one token per decode step in a neighbouring slot (all
+    256 slots occupied, sampled layers).  Against the oracle: layer 0's keys and values of sampled
+    positions, which depend on the embedding row, the first norm, the QKV projection and the rotation
+    only, so the oracle can compute them one by one at full width."""
+    eng, blob, m, spec, seed = full
+    n_prompt = 300
+    out = eng.decode_step()
+    victims = [int(s) for s in out["slot"][:2]]
+    for s in victims:
+        eng.retire_sequence(s)
+    prompt = synth.random_prompts(np.random.default_rng(41), 1, n_prompt, m.vocab)[0]
+    a = eng.add_sequence(900001, prompt, 2000)
+    b = eng.add_sequence(900002, prompt, 2000)
+    assert eng.prefill(a) == n_prompt - 1
+    for _ in range(n_prompt - 1):                    # slot b reads its prompt token by token; slot a generates
+        o = eng.decode_step()
+        for s in [int(s) for s, f in zip(o["slot"], o["finished"]) if f]:   # keep the batch full
+            eng.retire_sequence(s)
+            eng.add_sequence(910000 + s, prompt[:4], 2000)
+    layers = [0, m.n_layers // 2, m.n_layers - 1]
+    kv_a = {l: eng.debug_read_kv(a, l, n_prompt - 1) for l in layers}
+    kv_b = {l: eng.debug_read_kv(b, l, n_prompt - 1) for l in layers}
+    for l in layers:
+        assert np.array_equal(kv_a[l][0], kv_b[l][0]) and np.array_equal(kv_a[l][1], kv_b[l][1]), l
+        assert np.isfinite(kv_a[l][0]).all() and np.abs(kv_a[l][0]).max() > 0
+    # layer 0 against the oracle at sampled positions
+    w0 = eng.unpack_weights(blob, synth.bf16_bits_to_f32, names={"l0.g1", "l0.w_qkv"})
+    embed = eng.unpack_weights(blob, synth.bf16_bits_to_f32, names={"embed"})["embed"]
+    for p in [0, 1, 127, 128, 255, 256, n_prompt - 2]:
+        h = embed[int(prompt[p])].astype(np.float64)
+        x = decoder.rmsnorm(h, w0["l0.g1"].astype(np.float64), m.rms_eps)
+        k = decoder.rope((w0["l0.wk"].astype(np.float64) @ x).reshape(m.n_kv_heads, m.head_dim), p, m.rope_theta)
+        v = (w0["l0.wv"].astype(np.float64) @ x).reshape(m.n_kv_heads, m.head_dim)
+        scale = max(1.0, float(np.abs(k).max()))
+        ok, err = close(kv_a[0][0][p], k, 2e-2 * scale, 1e-2)
+        assert ok, ("K", p, err)
+        ok, err = close(kv_a[0][1][p], v, 2e-2 * scale, 1e-2)
+        assert ok, ("V", p, err)
