@@ -110,6 +110,27 @@ def test_attention_full_microbench_shape_on_sampled_rows():
         assert ok, (b, int(ctx[b]), err)
 
 
+def test_attention_chunk_boundaries_in_the_benchmark_launch_shape():
+    """Batch 256, 28 q / 4 kv heads, head_dim 128, 128-token pages, contexts up to 512 + 16384: the launch
+    shape of the 7B benchmark, where one workgroup handles up to 8192 tokens.  Contexts on both sides of
+    one and two full chunks, and the maximum, against the oracle; the merge of two and three chunks is on
+    the path of the last five."""
+    rng = np.random.default_rng(99)
+    Hq, Hkv, hd, pt = 28, 4, 128, 128
+    edges = [8191, 8192, 8193, 16383, 16384, 16385, 16896, 1, 128, 129]
+    ctx = np.concatenate([edges, rng.integers(200, 3000, 256 - len(edges))]).astype(np.int32)
+    rows = list(range(len(edges)))
+    pool, table, pps, known = _paged_inputs(rng, ctx, Hq, Hkv, hd, pt, rows)
+    q = synth.bf16_round(rng.standard_normal((256, Hq, hd)).astype(np.float32))
+    got = _run_attention(q, pool, table, ctx, Hq, Hkv, hd, pt, pps, 16896)
+    assert np.isfinite(got).all()
+    for b in rows:
+        K, V = known[b]
+        ref = decoder.attend_one(q[b].astype(np.float64), K.astype(np.float64), V.astype(np.float64))
+        ok, err = close(got[b], ref, ATOL, RTOL)
+        assert ok, (b, int(ctx[b]), err)
+
+
 GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 1024, 4), (3, 256, 1024, 2), (33, 320, 256, 1), (64, 2048, 1536, 3),
                (130, 1536, 8960, 7), (256, 4608, 3584, 7), (200, 3584, 18944, 8), (256, 3584, 18944, 9), (256, 2560, 3584, 1),
                (300, 640, 512, 2), (256, 33792, 256, 1), (130, 34000 // 32 * 32, 256, 1),
