@@ -326,8 +326,8 @@ def main():
     ap.add_argument("--batch-study", action="store_true",
                     help="instead of the benchmark line: throughput against batch size and a replay of a stage without refill")
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=1024)
+    ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
     ap.add_argument("--prefill", default="batched", choices=["batched", "decode"],
                     help="how a refilled slot reads its prompt: batched passes at admission, or one token per decode step")
