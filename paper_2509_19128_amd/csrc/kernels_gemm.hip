@@ -241,9 +241,12 @@ int launch_cfg(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, i
 int gemm_pick_splits(int M, int N, int K) {
   // One workgroup fits on a compute unit: split K so that the output tiles times the number of
   // slices comes close to, but not above, the 256 units, with at least 4 k-steps per slice.
+  int total = K / (4 * BK), best = 1;   // slices are made of groups of 4 k-steps
+  // Short K at 129..256 rows: 128 x 128 tiles, two workgroups per unit, four slices (measured best
+  // for the QKV and O projections of the 7B shape: fewer partial sums to write and to add up).
+  if (M > 128 && M <= 256 && K <= 4096 && total >= 4 && 3 * ((total + 3) / 4) < total) return 4;
   int bn = M > 128 ? 128 : 256;
   int tiles = ((N + bn - 1) / bn) * ((M + 255) / 256);
-  int total = K / (4 * BK), best = 1;   // slices are made of groups of 4 k-steps
   for (int s = 2; s <= 32 && tiles * s <= 256; ++s) {
     int c = (total + s - 1) / s;
     if ((s - 1) * c >= total) continue;   // slices must be non-empty
@@ -275,6 +278,7 @@ int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, 
     }
     return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s, true);
   }
+  if (M <= 256 && splits > 1 && K <= 4096) return launch_cfg<2, 2, 2, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
   // otherwise 256 x 128 tiles, one per compute unit and round
   return launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
 }

@@ -134,7 +134,7 @@ def test_attention_chunk_boundaries_in_the_benchmark_launch_shape():
 GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 1024, 4), (3, 256, 1024, 2), (33, 320, 256, 1), (64, 2048, 1536, 3),
                (130, 1536, 8960, 7), (256, 4608, 3584, 7), (200, 3584, 18944, 8), (256, 3584, 18944, 9), (256, 2560, 3584, 1),
                (300, 640, 512, 2), (256, 33792, 256, 1), (130, 34000 // 32 * 32, 256, 1),
-               (256, 43552, 256, 1), (129, 32768, 512, 1)]   # the last four take the paired 128 x 256 tiles
+               (256, 43552, 256, 1), (129, 32768, 512, 1), (200, 3584, 3584, 4), (256, 2048, 1536, 3)]   # the last four take the paired 128 x 256 tiles
 
 
 @pytest.mark.parametrize("M,N,K,splits", GEMM_SHAPES)
