@@ -217,9 +217,9 @@ def test_post_swap_steps_follow_new_weights_over_the_retained_cache(weights):
     eng.close()
 
 
-@pytest.mark.parametrize("name,batch,ctx", [("1p5b", 2, 48), ("7b", 2, 40)])
+@pytest.mark.parametrize("name,batch,ctx", [("1p5b", 2, 48), ("7b", 2, 40), ("32b", 2, 20)])
 def test_one_layer_slice_of_the_large_shapes(name, batch, ctx):
-    """One layer + LM head at the 1.5B / 7B shapes (real head counts, widths and vocabulary), a couple
+    """One layer + LM head at the 1.5B / 7B / 32B shapes (real head counts, widths and vocabulary), a couple
     of rows, short contexts: the oracle runs in float32 here to bound its memory."""
     m = synth.CONFIGS[name].with_layers(1)
     w = synth.make_weights(m, seed=4321)
@@ -241,7 +241,7 @@ def test_one_layer_slice_of_the_large_shapes(name, batch, ctx):
             for i, r in enumerate(recs):
                 ref = orc.last_logits[r.slot]
                 # The absolute tolerance is quoted for the tiny configuration, whose logits have rms 0.32
-                # (0.02 sqrt(256)); these shapes give rms 0.78 / 1.2, and the bf16 rounding error of a layer
+                # (0.02 sqrt(256)); these shapes give rms 0.78 / 1.2 / 1.4, and the bf16 rounding error of a layer
                 # is proportional to the logit scale, so the absolute part is scaled by that ratio.  The
                 # error rms itself must stay below 1 % of the logit rms (a wrong index or head mapping
                 # gives errors of order 100 %).
