@@ -229,13 +229,34 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
   const int64_t base = ((int64_t)b * p.Hkv + g) * p.max_chunks;
   for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
     const int h = idx / HD, d = idx % HD;
+    const float *ml = p.part_ml + (base * G + h) * 2;     // chunk c at ml[c * G * 2]
+    const float *po = p.part_o + (base * G + h) * HD + d; // chunk c at po[c * G * HD]
+    // loads of up to 8 chunks are issued together; the sums stay in chunk order
     float M = -INFINITY;
-    for (int c = 0; c < nchunk; ++c) M = fmaxf(M, p.part_ml[((base + c) * G + h) * 2]);
+    for (int c0 = 0; c0 < nchunk; c0 += 8) {
+      float m8[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) m8[u] = c0 + u < nchunk ? ml[(int64_t)(c0 + u) * G * 2] : -INFINITY;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) M = fmaxf(M, m8[u]);
+    }
     float L = 0.f, O = 0.f;
-    for (int c = 0; c < nchunk; ++c) {
-      float f = __builtin_amdgcn_exp2f(p.part_ml[((base + c) * G + h) * 2] - M);
-      L += p.part_ml[((base + c) * G + h) * 2 + 1] * f;
-      O += p.part_o[((base + c) * G + h) * HD + d] * f;
+    for (int c0 = 0; c0 < nchunk; c0 += 8) {
+      float m8[8], l8[8], o8[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (c0 + u < nchunk) {
+          m8[u] = ml[(int64_t)(c0 + u) * G * 2];
+          l8[u] = ml[(int64_t)(c0 + u) * G * 2 + 1];
+          o8[u] = po[(int64_t)(c0 + u) * G * HD];
+        }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (c0 + u < nchunk) {
+          const float f = __builtin_amdgcn_exp2f(m8[u] - M);
+          L += l8[u] * f;
+          O += o8[u] * f;
+        }
     }
     p.out[((int64_t)b * p.Hq + g * G + h) * HD + d] = (__bf16)(O / L);
   }
