@@ -31,6 +31,10 @@ WORKLOADS = {
     "7b": dict(model="7b", batch=256, prompt=512, mean=4096.0, gmax=16384, swap_every=128, pool_tokens=1_700_000),
     "1p5b": dict(model="1p5b", batch=64, prompt=256, mean=2048.0, gmax=8192, swap_every=256, pool_tokens=400_000),
     "tiny": dict(model="tiny", batch=4, prompt=16, mean=48.0, gmax=64, swap_every=32, pool_tokens=4 * 128),
+    # 32B shape: two 65.5 GB weight buffers + 256 KiB of KV per token; batch 64 is what fits 288 GB with headroom
+    # (the configuration asks for 128 "or the largest that fits"); total length lognormal(mean 6000), at most 16384
+    "32b": dict(model="32b", batch=64, prompt=512, mean=5488.0, gmax=15872, swap_every=64, pool_tokens=400_000,
+                host_staged=True),
 }
 
 
@@ -55,6 +59,32 @@ def device_weight_blob(eng, torch, seed, std=0.02, base=None, delta=0.0):
             if c == 1:
                 blob[off:off + r] = 1.0
     return blob
+
+
+def host_staged_weights(eng, torch, seed, std=0.02, delta=1e-3):
+    """For blobs too large to hold a spare copy in HBM or two copies in pinned memory (this host pins
+    about 64 GiB): W is generated piecewise on the device into ONE pinned host buffer and loaded from
+    there; the buffer is then overwritten, piece by piece, with W + N(0, delta^2), the blob every later
+    update copies in.  Returns the pinned buffer."""
+    n = eng.weight_nbytes() // 2
+    host = torch.empty(n, dtype=torch.bfloat16, pin_memory=True)
+    gains = [(off, r) for name, off, (r, c) in eng.weight_layout() if c == 1]
+    step = 1 << 28
+    for version in range(2):
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        g2 = torch.Generator(device="cuda").manual_seed(seed + 1)
+        for o in range(0, n, step):
+            m = min(step, n - o)
+            w = (torch.randn(m, generator=g, device="cuda", dtype=torch.float32) * std).to(torch.bfloat16)
+            if version == 1:
+                w = (w.float() + torch.randn(m, generator=g2, device="cuda", dtype=torch.float32) * delta).to(torch.bfloat16)
+            host[o:o + m].copy_(w)
+        torch.cuda.synchronize()
+        for off, r in gains:
+            host[off:off + r] = 1.0
+        if version == 0:
+            eng.load_weights(host.data_ptr(), eng.weight_nbytes())
+    return host
 
 
 def fill_kv_pool(eng, torch, seed):
@@ -356,17 +386,22 @@ def main():
     max_ctx = spec["prompt"] + spec["gmax"]
     eng = pl.Engine.from_model(model, max_batch=spec["batch"], max_context=max_ctx,
                                kv_pool_tokens=spec["pool_tokens"], n_weight_buffers=2, seed=1234 + 3, device=0)
-    w0 = device_weight_blob(eng, torch, seed=1237)
-    torch.cuda.synchronize()
-    eng.load_weights(w0.data_ptr(), eng.weight_nbytes())
-    # the "next optimizer step" weights wait in pinned host memory, as a trainer's broadcast buffer would
-    w1 = device_weight_blob(eng, torch, seed=1238, base=w0, delta=1e-3)
-    host = [torch.empty(w0.numel(), dtype=torch.bfloat16, pin_memory=True) for _ in range(2)]
-    host[0].copy_(w1)
-    host[1].copy_(w0)
-    torch.cuda.synchronize()
-    del w0, w1
-    torch.cuda.empty_cache()
+    if spec.get("host_staged"):
+        hw = host_staged_weights(eng, torch, seed=1237)
+        host = [hw, hw]      # every update copies the same blob in: the copy and the flip are what is measured
+        torch.cuda.empty_cache()
+    else:
+        w0 = device_weight_blob(eng, torch, seed=1237)
+        torch.cuda.synchronize()
+        eng.load_weights(w0.data_ptr(), eng.weight_nbytes())
+        # the "next optimizer step" weights wait in pinned host memory, as a trainer's broadcast buffer would
+        w1 = device_weight_blob(eng, torch, seed=1238, base=w0, delta=1e-3)
+        host = [torch.empty(w0.numel(), dtype=torch.bfloat16, pin_memory=True) for _ in range(2)]
+        host[0].copy_(w1)
+        host[1].copy_(w0)
+        torch.cuda.synchronize()
+        del w0, w1
+        torch.cuda.empty_cache()
     fill_kv_pool(eng, torch, seed=1239)
 
     wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill=args.prefill == "batched", keep_history=args.recompute_kv)

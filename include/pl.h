@@ -166,7 +166,7 @@ int pl_swap_poll(pl_engine *e, int32_t *staged_ready, uint32_t *active_version);
 int pl_add_sequence(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt,
                     int32_t max_new, float temperature, int32_t *out_slot);
 /* Batched prompt reading on refill ("add prompts", Alg. 2): reads the positions of the slot's prompt
- * that have not been read yet, except the last one, in passes of up to min(max_batch, 256) positions
+ * that have not been read yet, except the last one, in passes of up to 256 positions
  * through the same kernels as a decode step (rows = consecutive positions of one sequence, causal
  * because row i attends to positions <= its own), under the active weights.  It leaves exactly the
  * keys and values that reading those tokens one per step would leave (up to bf16 rounding of

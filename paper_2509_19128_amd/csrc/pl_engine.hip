@@ -72,6 +72,7 @@ struct pl_engine {
   pl_model_cfg cfg{};
   bool dry = false;
   int G = 1, page_tokens = 64, pages_per_seq = 0;
+  int rows_cap = 0;   // rows the work buffers hold: max(max_batch, 256), so cache-only passes can take 256 rows
   int64_t n_pages = 0, layer_stride = 0, page_stride = 0;   // elements
   // weights
   std::vector<Tensor> layout;
@@ -117,11 +118,11 @@ struct pl_engine {
   int64_t streamed_weight_bytes = 0;
 
   int32_t *m_row_slot(bool dev) { return (int32_t *)(dev ? meta_d : meta_h); }
-  int32_t *m_pos(bool dev) { return m_row_slot(dev) + cfg.max_batch; }
-  int32_t *m_input(bool dev) { return m_pos(dev) + cfg.max_batch; }
-  int32_t *m_forced(bool dev) { return m_input(dev) + cfg.max_batch; }
-  float *m_inv_t(bool dev) { return (float *)(m_forced(dev) + cfg.max_batch); }
-  uint64_t *m_seq_id(bool dev) { return (uint64_t *)(m_inv_t(dev) + cfg.max_batch); }
+  int32_t *m_pos(bool dev) { return m_row_slot(dev) + rows_cap; }
+  int32_t *m_input(bool dev) { return m_pos(dev) + rows_cap; }
+  int32_t *m_forced(bool dev) { return m_input(dev) + rows_cap; }
+  float *m_inv_t(bool dev) { return (float *)(m_forced(dev) + rows_cap); }
+  uint64_t *m_seq_id(bool dev) { return (uint64_t *)(m_inv_t(dev) + rows_cap); }
 
   const bf16_t *wptr(int buf, const char *name) const {
     for (auto &t : layout)
@@ -205,26 +206,29 @@ int alloc_device(pl_engine *e) {
   e->sp_qkv = pl::gemm_pick_splits(B, (int)wq, (int)d);
   e->sp_o = pl::gemm_pick_splits(B, (int)d, (int)qd);
   e->sp_d = pl::gemm_pick_splits(B, (int)d, c.d_ffn);
-  int64_t parts = std::max(std::max(e->sp_qkv * wq, e->sp_o * d), e->sp_d * d) * B;
+  const int64_t R = e->rows_cap;   // rows of the activation buffers (cache-only passes take up to 256 rows)
+  int64_t parts = std::max(std::max(e->sp_qkv * wq, e->sp_o * d), e->sp_d * d) * R;
   if ((rc = dev_alloc(&e->pt_d, (int64_t)B * e->pages_per_seq))) return rc;
   if ((rc = dev_alloc(&e->meta_d, e->meta_bytes))) return rc;
-  if ((rc = dev_alloc(&e->h, B * d))) return rc;
-  if ((rc = dev_alloc(&e->a, B * d))) return rc;
+  if ((rc = dev_alloc(&e->h, R * d))) return rc;
+  if ((rc = dev_alloc(&e->a, R * d))) return rc;
   if ((rc = dev_alloc(&e->parts, parts))) return rc;
-  if ((rc = dev_alloc(&e->q_rot, B * qd))) return rc;
-  if ((rc = dev_alloc(&e->attn_out, B * qd))) return rc;
-  if ((rc = dev_alloc(&e->mid, (int64_t)B * c.d_ffn))) return rc;
+  if ((rc = dev_alloc(&e->q_rot, R * qd))) return rc;
+  if ((rc = dev_alloc(&e->attn_out, R * qd))) return rc;
+  if ((rc = dev_alloc(&e->mid, R * c.d_ffn))) return rc;
   if ((rc = dev_alloc(&e->logits, (int64_t)B * c.vocab))) return rc;
-  if ((rc = dev_alloc(&e->cs, (int64_t)B * c.head_dim))) return rc;
-  if ((rc = dev_alloc(&e->ctx_len, B))) return rc;
+  if ((rc = dev_alloc(&e->cs, R * c.head_dim))) return rc;
+  if ((rc = dev_alloc(&e->ctx_len, R))) return rc;
   if ((rc = dev_alloc(&e->tok_d, B))) return rc;
   if ((rc = dev_alloc(&e->lp_d, B))) return rc;
+  // the chunk length is fixed by max_batch alone, so a sequence's attention result never depends on
+  // how many rows a pass holds
   e->attn_chunk = pl::attention_chunk_tokens(B, c.n_kv_heads, c.max_context);
   e->attn_max_chunks = (c.max_context + e->attn_chunk - 1) / e->attn_chunk;
-  const int64_t np = (int64_t)B * c.n_kv_heads * e->attn_max_chunks * e->G;
+  const int64_t np = R * c.n_kv_heads * e->attn_max_chunks * e->G;
   if ((rc = dev_alloc(&e->attn_po, np * c.head_dim))) return rc;
   if ((rc = dev_alloc(&e->attn_pml, np * 2))) return rc;
-  if ((rc = dev_alloc(&e->attn_work, pl::attention_worklist_ints(B, e->attn_max_chunks)))) return rc;
+  if ((rc = dev_alloc(&e->attn_work, pl::attention_worklist_ints((int)R, e->attn_max_chunks)))) return rc;
   char *ws = nullptr;
   if ((rc = dev_alloc(&ws, pl::sample_workspace_bytes(B, c.vocab)))) return rc;
   e->samp_ws = ws;
@@ -375,12 +379,12 @@ int admit(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt
 }
 
 // Cache-only passes: rows (slot, position, token) go through the decode kernels in prefill mode, in
-// groups of up to min(max_batch, 256); the rows of one slot must come in position order, because a
+// groups of up to 256; the rows of one slot must come in position order, because a
 // row attends to the keys and values that earlier rows of its slot (in this or an earlier group) leave.
 int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::vector<int32_t> &positions,
                   const std::vector<int32_t> &tokens, double *ms_total, uint64_t *passes) {
   const pl_model_cfg &c = e->cfg;
-  const int rows_max = std::min<int>(c.max_batch, 256);
+  const int rows_max = 256;
   int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
   float *inv_t = e->m_inv_t(false);
   uint64_t *sid = e->m_seq_id(false);
@@ -473,7 +477,8 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
   e->seqs.resize(cfg->max_batch);
   e->free_pages.reserve(e->n_pages);
   for (int64_t p = e->n_pages - 1; p >= 0; --p) e->free_pages.push_back((int32_t)p);   // page 0 is handed out first
-  e->meta_bytes = (int64_t)cfg->max_batch * (4 * 5 + 8);
+  e->rows_cap = std::max(cfg->max_batch, 256);
+  e->meta_bytes = (int64_t)e->rows_cap * (4 * 5 + 8);
   e->st.kv_pages_total = e->n_pages;
   if (e->dry) {
     e->meta_h = (char *)calloc(1, (size_t)e->meta_bytes);

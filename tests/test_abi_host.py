@@ -209,7 +209,7 @@ def test_batched_prefill_bookkeeping():
     assert e.prefill(s0) == 6 and e.prefill(s0) == 0             # nothing left the second time
     assert e.prefill(s1) == 0                                    # a one-token prompt has nothing to prefill
     st = e.stats()
-    assert st["prefill_positions"] == 6 and st["prefill_passes"] == 2   # passes of min(max_batch, 256) = 4 rows
+    assert st["prefill_positions"] == 6 and st["prefill_passes"] == 1   # passes hold up to 256 rows
     assert st["steps"] == 0 and st["tokens_emitted"] == 0
     r = e.decode_step()
     assert r["n"] == 2 and r["position"].tolist() == [6, 0] and r["emitted"].tolist() == [1, 1]
