@@ -349,8 +349,74 @@ def is_ess_study(args):
                                        "sample": f"first {k} sequences ({int(off[k])} tokens) of the same batch"}}))
 
 
+def attention_microbench(args):
+    """One decode-attention step over a paged bf16 cache: batch 512, 28 q / 4 kv heads, head_dim 128,
+    contexts lognormal(4096) clipped to [128, 16384], q/K/V ~ N(0,1); median over `--steps` launches (the
+    4 GB of K/V exceed every cache, so consecutive launches do not help each other).  One JSON line."""
+    import torch
+    import paper_2509_19128_amd as pl
+    from oracle import decoder
+
+    B, Hq, Hkv, hd, pt = 512, 28, 4, 128, 128
+    ctx = synth.attention_microbench_lengths(1236).astype(np.int32)
+    need = (ctx + pt - 1) // pt
+    n_pages, pps = int(need.sum()) + 4, int(need.max())
+    rng = np.random.default_rng(0)
+    perm = rng.permutation(n_pages).astype(np.int32)
+    table = np.zeros((B, pps), np.int32)
+    k = 0
+    for b in range(B):
+        table[b, :need[b]] = perm[k:k + need[b]]
+        k += need[b]
+    pe = Hkv * 2 * pt * hd
+    pool = torch.empty(n_pages * pe, device="cuda", dtype=torch.bfloat16)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    for o in range(0, n_pages * pe, 1 << 28):
+        m = min(1 << 28, n_pages * pe - o)
+        pool[o:o + m] = torch.randn(m, generator=g, device="cuda").to(torch.bfloat16)
+    q = torch.randn(B, Hq, hd, generator=g, device="cuda").to(torch.bfloat16)
+    out = torch.zeros(B, Hq, hd, device="cuda", dtype=torch.bfloat16)
+    ws = torch.empty(pl.pl_attention_workspace_bytes(B, Hq, Hkv, hd, int(ctx.max())), device="cuda", dtype=torch.uint8)
+    tb, cl = torch.from_numpy(table).cuda(), torch.from_numpy(ctx).cuda()
+    s = torch.cuda.current_stream()
+    times = []
+    for i in range(args.warmup + args.steps):
+        a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(s)
+        pl.pl_attention_decode(q.data_ptr(), pool.data_ptr(), tb.data_ptr(), cl.data_ptr(), out.data_ptr(), ws.data_ptr(),
+                               B, Hq, Hkv, hd, pt, pps, int(ctx.max()), s.cuda_stream)
+        e.record(s)
+        torch.cuda.synchronize()
+        if i >= args.warmup:
+            times.append(a.elapsed_time(e))
+    ms = float(np.median(times))
+    nbytes = float(ctx.sum()) * Hkv * hd * 2 * 2
+    # oracle on a bounded sample: the shortest sequences of the batch, one by one, float64
+    order = np.argsort(ctx)[:8]
+    t0 = time.perf_counter()
+    toks = 0
+    for b in order:
+        c = int(ctx[b])
+        K, V = rng.standard_normal((c, Hkv, hd)), rng.standard_normal((c, Hkv, hd))
+        decoder.attend_one(rng.standard_normal((Hq, hd)), K, V)
+        toks += c
+    t_cpu = time.perf_counter() - t0
+    print(json.dumps({"metric": "decode attention, K/V bytes per second", "value": nbytes / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                      "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "decode-attention microbenchmark: batch 512, 28 q / 4 kv heads, head_dim 128, "
+                                             "contexts lognormal(4096) in [128, 16384], 128-token pages", "mean_context": float(ctx.mean())},
+                      "roofline": {"bound": "hbm", "kernel": "attn_worklist_kernel + attn_decode_kernel + attn_combine_kernel",
+                                   "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                   "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": nbytes},
+                      "cpu_baseline": {"value": toks * Hkv * hd * 4 / t_cpu / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                       "sample": f"the 8 shortest sequences ({toks} cached tokens), float64, counted at 2 bytes per element"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--attn-microbench", action="store_true",
+                    help="instead of the benchmark line: the decode-attention microbenchmark (batch 512, one step)")
     ap.add_argument("--is-ess", action="store_true",
                     help="instead of the benchmark line: time the importance-weight / ESS reduction on one optimizer batch")
     ap.add_argument("--batch-study", action="store_true",
@@ -377,6 +443,8 @@ def main():
         return batch_study(args)
     if args.is_ess:
         return is_ess_study(args)
+    if args.attn_microbench:
+        return attention_microbench(args)
 
     import torch
     import paper_2509_19128_amd as pl

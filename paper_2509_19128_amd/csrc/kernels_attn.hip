@@ -177,44 +177,61 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   }
 }
 
+// Inclusive prefix sum over the 1024 threads of the workgroup (wave shuffles, then the 16 wave totals).
+__device__ inline int block_scan_1024(int v, int *wsum, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(v, o, 64);
+    if (lane >= o) v += t;
+  }
+  __syncthreads();   // wsum may still be read from a previous call
+  if (lane == 63) wsum[wave] = v;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int x = wsum[w];
+    all += x;
+    if (w < wave) before += x;
+  }
+  *total = all;
+  return v + before;
+}
+
 // work[0] = number of items, then (sequence, chunk) pairs: all full chunks, then each sequence's
-// last (partial or full) chunk.  One workgroup; n_seq <= 1024.
+// last (partial or full) chunk, longest first, so that the workgroups still running when the grid
+// drains are the short ones.  One workgroup; n_seq <= 1024.
 __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_len, int32_t *work, int n_seq,
                                                              int chunk) {
-  __shared__ int sc[1024];
+  __shared__ int wsum[16];
+  __shared__ __attribute__((aligned(16))) int tail[1024];
   const int b = threadIdx.x;
-  const int n = b < n_seq ? (ctx_len[b] + chunk - 1) / chunk : 0;
+  const int ctx = b < n_seq ? ctx_len[b] : 0;
+  const int n = (ctx + chunk - 1) / chunk;
   const int full = n > 0 ? n - 1 : 0;
-  // inclusive scan of the full-chunk counts
-  sc[b] = full;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = b >= o ? sc[b - o] : 0;
-    __syncthreads();
-    sc[b] += v;
-    __syncthreads();
-  }
-  const int total_full = sc[1023];
-  int at = sc[b] - full;
+  int total_full, n_last;
+  const int at = block_scan_1024(full, wsum, &total_full) - full;
   for (int c = 0; c < full; ++c) { work[1 + 2 * (at + c)] = b; work[2 + 2 * (at + c)] = c; }
-  __syncthreads();
-  // then the last chunks, longest first, so that the workgroups still running when the grid drains
-  // are the short ones
-  __shared__ int tail[1024];
-  const int rem = n > 0 ? ctx_len[b] - (n - 1) * chunk : 0;
-  tail[b] = rem;
-  sc[b] = n > 0;
-  __syncthreads();
-  int rank = 0;
-  for (int o = 0; o < n_seq; ++o) rank += (tail[o] > rem) || (tail[o] == rem && o < b && tail[o] > 0);
-  if (n > 0) { const int i = total_full + rank; work[1 + 2 * i] = b; work[2 + 2 * i] = n - 1; }
-  for (int o = 1; o < 1024; o <<= 1) {
-    int v = b >= o ? sc[b - o] : 0;
-    __syncthreads();
-    sc[b] += v;
-    __syncthreads();
+  const int rem = n > 0 ? ctx - (n - 1) * chunk : 0;
+  tail[b] = rem;   // 0 for empty rows and for threads at or beyond n_seq
+  (void)block_scan_1024(n > 0, wsum, &n_last);   // also orders the writes to tail before the reads below
+  if (n > 0) {   // rank among the last chunks: longer first, lower sequence index first among equals
+    int rank = 0;
+    const int4 *t4 = (const int4 *)tail;
+    for (int o4 = 0; o4 < (n_seq + 3) / 4; ++o4) {
+      const int4 t = t4[o4];
+      const int o = o4 * 4;
+      rank += (t.x > rem) || (t.x == rem && o < b);
+      rank += (t.y > rem) || (t.y == rem && o + 1 < b);
+      rank += (t.z > rem) || (t.z == rem && o + 2 < b);
+      rank += (t.w > rem) || (t.w == rem && o + 3 < b);
+    }
+    const int i = total_full + rank;
+    work[1 + 2 * i] = b;
+    work[2 + 2 * i] = n - 1;
   }
-  if (b == 0) work[0] = total_full + sc[1023];
+  if (b == 0) work[0] = total_full + n_last;
 }
 
 // Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup per (sequence, kv
