@@ -131,6 +131,20 @@ def test_attention_chunk_boundaries_in_the_benchmark_launch_shape():
         assert ok, (b, int(ctx[b]), err)
 
 
+def test_attention_rejects_bad_arguments():
+    t = torch.zeros(1 << 16, device="cuda", dtype=torch.bfloat16)
+    p = t.data_ptr()
+    good = dict(n=2, Hq=8, Hkv=2, hd=32, pt=32, pps=4, mx=128)
+    for bad in [dict(Hq=7), dict(hd=48), dict(pt=48), dict(pt=16), dict(mx=129), dict(mx=0), dict(n=0), dict(n=2000), dict(Hq=40, Hkv=2)]:
+        a = dict(good, **bad)
+        with pytest.raises(pl.PlError) as ex:
+            pl.pl_attention_decode(p, p, p, p, p, p, a["n"], a["Hq"], a["Hkv"], a["hd"], a["pt"], a["pps"], a["mx"], 0)
+        assert ex.value.code == pl.PL_E_INVAL, bad
+    with pytest.raises(pl.PlError):
+        pl.pl_attention_decode(0, p, p, p, p, p, 2, 8, 2, 32, 32, 4, 128, 0)
+    assert pl.pl_attention_workspace_bytes(0, 8, 2, 32, 128) == 0
+
+
 GEMM_SHAPES = [(4, 384, 256, 1), (4, 4096, 1024, 4), (3, 256, 1024, 2), (33, 320, 256, 1), (64, 2048, 1536, 3),
                (130, 1536, 8960, 7), (256, 4608, 3584, 7), (200, 3584, 18944, 8), (256, 3584, 18944, 9), (256, 2560, 3584, 1),
                (300, 640, 512, 2), (256, 33792, 256, 1), (130, 34000 // 32 * 32, 256, 1),
