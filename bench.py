@@ -480,7 +480,7 @@ def main():
     torch.cuda.synchronize()
     s0 = eng.stats()
     emitted = 0
-    step_ms, stalls, flips = [], [], []
+    step_ms, stalls, flips, requests = [], [], [], []
     swaps_requested = 0
     last_version = s0["active_version"]
     t0 = time.perf_counter()
@@ -489,6 +489,7 @@ def main():
             try:    # Alg. 2: the trainer requests an update; the engine stages it while decoding goes on
                 eng.swap_weights(host[swaps_requested % 2].data_ptr(), eng.weight_nbytes(), flags=pl.PL_SWAP_ASYNC | (pl.PL_SWAP_RECOMPUTE_KV if args.recompute_kv else 0))
                 swaps_requested += 1
+                requests.append(k)
             except pl.PlError as ex:
                 if ex.code != pl.PL_E_BUSY:
                     raise
@@ -525,6 +526,12 @@ def main():
         around = np.concatenate([sm[lo:k], sm[k + 1:hi]])
         if len(around):
             stall_ms = max(stall_ms, float(sm[k] - np.median(around)) + float(stalls[k]))
+    # interference: decode steps that run while a staging copy is in flight (request .. flip) against the rest
+    during = np.zeros(len(sm), bool)
+    for rq in requests:
+        fl = [f for f in flips if f >= rq]
+        during[rq:(fl[0] if fl else len(sm))] = True
+    interference = float(sm[during].mean() - sm[~during].mean()) if during.any() and (~during).any() else 0.0
     res = {
         "metric": "generated tokens/s/GPU at constant batch", "value": emitted / wall, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps,
@@ -541,6 +548,7 @@ def main():
                      "achieved_GBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6,
                      "frac_of_8TBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6 / HBM_PEAK_GBS},
         "swap": {"requested": swaps_requested, "flips_at_steps": flips, "stall_ms": stall_ms,
+                 "steps_overlapping_a_copy": int(during.sum()), "interference_ms_per_overlapping_step": interference,
                  "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9,
                  "kv_cache": "recomputed at the flip" if args.recompute_kv else "kept",
                  "recompute_positions": s1["recompute_positions"] - s0["recompute_positions"],
