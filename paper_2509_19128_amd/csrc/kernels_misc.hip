@@ -38,18 +38,33 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const bf16_t *embed,
     a[(int64_t)row * d + i] = (__bf16)(h[(int64_t)row * d + i] * r * (float)g[i]);
 }
 
+template <int NW>
+__device__ inline float block_sum(float v) {
+  __shared__ float red[NW];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) t += red[w];
+  return t;
+}
+
 // h[row] += sum_s parts[s][row]; a[row] = rmsnorm(h[row]) * g.  Partials are added in slice order.
-// The row (d <= 8192) stays in registers between the two passes; all loads are 16 bytes wide.
-__global__ __launch_bounds__(256) void resid_rmsnorm_kernel(float *h, const float *parts, int splits,
-                                                            const bf16_t *g, bf16_t *a, int n, int d, float eps) {
-  constexpr int NV = 8;
+// One workgroup of NT threads per row, NV 16-byte pieces per thread (NT * NV * 4 >= d); the row stays in
+// registers between the two passes.
+template <int NT, int NV>
+__global__ __launch_bounds__(NT) void resid_rmsnorm_kernel(float *h, const float *parts, int splits,
+                                                           const bf16_t *g, bf16_t *a, int n, int d, float eps) {
   const int row = blockIdx.x, d4 = d >> 2;
   float4 *h4 = (float4 *)(h + (int64_t)row * d);
   float4 v[NV];
   float ss = 0.f;
 #pragma unroll
   for (int it = 0; it < NV; ++it) {
-    const int idx = threadIdx.x + it * 256;
+    const int idx = threadIdx.x + it * NT;
     if (idx < d4) {
       float4 x = h4[idx];
       // loads of up to 8 slices are issued together, the adds stay in slice order
@@ -67,11 +82,11 @@ __global__ __launch_bounds__(256) void resid_rmsnorm_kernel(float *h, const floa
       ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
     }
   }
-  ss = block_sum_256(ss);
+  ss = block_sum<NT / 64>(ss);
   const float r = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
   for (int it = 0; it < NV; ++it) {
-    const int idx = threadIdx.x + it * 256;
+    const int idx = threadIdx.x + it * NT;
     if (idx < d4) {
       const bf16x4 gg = ((const bf16x4 *)g)[idx];
       bf16x4 o;
@@ -184,7 +199,12 @@ int launch_embed_rmsnorm(const bf16_t *embed, const bf16_t *g, const int32_t *in
 int launch_resid_rmsnorm(float *h, const float *parts, int splits, const bf16_t *g, bf16_t *a, int n, int d,
                          float eps, hipStream_t s) {
   if (n <= 0) return 0;
-  hipLaunchKernelGGL(resid_rmsnorm_kernel, dim3(n), dim3(256), 0, s, h, parts, splits, g, a, n, d, eps);
+  // rows of up to 4096 floats: 1024 threads, one 16-byte piece each (all loads of a row in flight at
+  // once); wider rows: 1024 threads x 2 pieces (d <= 8192)
+  if (d <= 4096)
+    hipLaunchKernelGGL((resid_rmsnorm_kernel<1024, 1>), dim3(n), dim3(1024), 0, s, h, parts, splits, g, a, n, d, eps);
+  else
+    hipLaunchKernelGGL((resid_rmsnorm_kernel<1024, 2>), dim3(n), dim3(1024), 0, s, h, parts, splits, g, a, n, d, eps);
   return ok();
 }
 
