@@ -400,3 +400,40 @@ def test_recomputed_cache_equals_the_cache_of_a_run_under_the_new_weights_from_t
         for l in range(M.n_layers):
             assert np.array_equal(ka[l][0], kb[l][0]) and np.array_equal(ka[l][1], kb[l][1]), (i, l)
     eng_a.close(); eng_b.close()
+
+
+def test_prefill_of_a_partly_read_prompt_and_of_neighbours_in_other_states(weights):
+    """pl_prefill picks up where token-by-token reading stopped; slots that are generating, or still
+    reading their own prompt token by token, are not disturbed by another slot's passes."""
+    master, _ = weights
+    orc = OracleEngine(M, _rounded(master), max_batch=4, seed=SEED)
+    eng = _engine()
+    eng.load_weights(eng.pack_weights(master, synth.f32_to_bf16_bits))
+    prompts = [synth.random_prompts(np.random.default_rng(60 + i), 1, n, M.vocab)[0] for i, n in enumerate([3, 40, 25])]
+    for i in range(3):
+        assert eng.add_sequence(300 + i, prompts[i], 30) == orc.add_sequence(300 + i, prompts[i], 30) == i
+
+    def both_step():
+        recs = orc.decode_step()
+        forced = np.full(4, -1, np.int32)
+        for r in recs:
+            forced[r.slot] = r.token
+        out = eng.decode_step(forced)
+        lg = eng.debug_get_logits(out["n"])
+        assert out["n"] == len(recs)
+        for i, r in enumerate(recs):
+            assert (out["slot"][i], out["position"][i], bool(out["emitted"][i])) == (r.slot, r.position, r.emitted)
+            ok, err = close(lg[i], orc.last_logits[r.slot], ATOL, RTOL)
+            assert ok, (r.slot, r.position, err)
+
+    for _ in range(6):                 # slot 0 is generating by now, slots 1 and 2 are 6 tokens into their prompts
+        both_step()
+    assert eng.prefill(1) == 40 - 1 - 6
+    s0, s2 = orc.slots[0], orc.slots[2]
+    orc.slots[0] = orc.slots[2] = None # the oracle reads the rest of slot 1's prompt alone, token by token
+    for _ in range(40 - 1 - 6):
+        orc.decode_step()
+    orc.slots[0], orc.slots[2] = s0, s2
+    for _ in range(8):
+        both_step()
+    eng.close()
