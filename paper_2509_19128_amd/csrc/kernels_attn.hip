@@ -26,21 +26,26 @@ template <int HD, int NS>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   constexpr int NJ = HD / 32;   // QK MFMAs per 16-token tile
   constexpr int NV = HD / 16;   // PV MFMAs per 32-token run
-  // Work items come from a compact list of (sequence, chunk) pairs built on the device for this
-  // step: every launched workgroup up to the list's length has work (full chunks first, the partial
-  // last chunks of the sequences at the end), so consecutive workgroup ids, which the hardware deals
-  // round-robin to the 8 XCDs, load all XCDs evenly whatever the mix of context lengths.
+  // Work items come from a compact list built on the device for this step: every launched workgroup
+  // up to the list's length has work (full chunks first, then the last chunks, longest first), so
+  // consecutive workgroup ids, which the hardware deals round-robin to the 8 XCDs, load all XCDs
+  // evenly whatever the mix of context lengths.  An item is one 32-byte record (sequence, chunk,
+  // context length, slot, and the first four page ids of the chunk), so that the first K/V loads of
+  // a workgroup are two dependent scalar loads away (list length, record) instead of five: with the
+  // memory system saturated each such load takes about a microsecond during which the workgroup has
+  // nothing in flight.
   const int item = blockIdx.x / p.Hkv, g = blockIdx.x % p.Hkv;
   if (item >= p.work[0]) return;
-  const int b = p.work[1 + 2 * item], c = p.work[2 + 2 * item];
-  const int ctx = p.ctx_len[b];
+  const int4 *rec = (const int4 *)(p.work + 8 + 8 * (int64_t)item);
+  const int4 r0 = rec[0], r1 = rec[1];
+  const int b = r0.x, c = r0.y, ctx = r0.z, slot = r0.w;
   const int t0 = c * p.chunk;
   const int t1 = min(ctx, t0 + p.chunk);
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int head = l & 15, qg = l >> 4;
   const int G = p.Hq / p.Hkv;
-  const int slot = p.row_slot ? p.row_slot[b] : b;
   const int32_t *pt = p.page_table + (int64_t)slot * p.pages_per_seq;
+  const int page_first = t0 / p.page_tokens;   // r1 holds the ids of pages page_first .. page_first + 3
   const float scale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(hd)
 
   // Query operand: column = head of the group (zero for the padding columns), k = head-dim slice.
@@ -64,7 +69,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   const int64_t page_elems = (int64_t)2 * p.page_tokens * HD;   // K block + V block of one kv head
   auto run_base = [&](int blk) -> const bf16_t * {
     int t = t0 + blk * 32;
-    int page = pt[t / p.page_tokens];
+    const int rel = t / p.page_tokens - page_first;
+    int page = rel == 0 ? r1.x : rel == 1 ? r1.y : rel == 2 ? r1.z : rel == 3 ? r1.w : pt[t / p.page_tokens];
     int r = (t % p.page_tokens) >> 5;
     return p.kv + ((int64_t)page * p.Hkv + g) * page_elems + (int64_t)r * 32 * HD + l * 8;
   };
@@ -199,20 +205,32 @@ __device__ inline int block_scan_1024(int v, int *wsum, int *total) {
   return v + before;
 }
 
-// work[0] = number of items, then (sequence, chunk) pairs: all full chunks, then each sequence's
-// last (partial or full) chunk, longest first, so that the workgroups still running when the grid
-// drains are the short ones.  One workgroup; n_seq <= 1024.
-__global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_len, int32_t *work, int n_seq,
-                                                             int chunk) {
+// work[0] = number of items; the items are 8-int records from work[8] on: {sequence, chunk, context
+// length, slot, ids of the chunk's first four pages}.  All full chunks come first, then each
+// sequence's last (partial or full) chunk, longest first, so that the workgroups still running when
+// the grid drains are the short ones.  One workgroup; n_seq <= 1024.
+__global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_len, const int32_t *row_slot,
+                                                             const int32_t *page_table, int32_t *work, int n_seq,
+                                                             int chunk, int page_tokens, int pages_per_seq) {
   __shared__ int wsum[16];
   __shared__ __attribute__((aligned(16))) int tail[1024];
   const int b = threadIdx.x;
   const int ctx = b < n_seq ? ctx_len[b] : 0;
+  const int slot = b < n_seq ? (row_slot ? row_slot[b] : b) : 0;
   const int n = (ctx + chunk - 1) / chunk;
   const int full = n > 0 ? n - 1 : 0;
+  const int32_t *pt = page_table + (int64_t)slot * pages_per_seq;
+  const int last_page = ctx > 0 ? (ctx - 1) / page_tokens : 0;
+  auto put = [&](int i, int c) {
+    int4 *rec = (int4 *)(work + 8 + 8 * (int64_t)i);
+    const int p0 = c * chunk / page_tokens;
+    rec[0] = make_int4(b, c, ctx, slot);
+    rec[1] = make_int4(pt[min(p0, last_page)], pt[min(p0 + 1, last_page)], pt[min(p0 + 2, last_page)],
+                       pt[min(p0 + 3, last_page)]);
+  };
   int total_full, n_last;
   const int at = block_scan_1024(full, wsum, &total_full) - full;
-  for (int c = 0; c < full; ++c) { work[1 + 2 * (at + c)] = b; work[2 + 2 * (at + c)] = c; }
+  for (int c = 0; c < full; ++c) put(at + c, c);
   const int rem = n > 0 ? ctx - (n - 1) * chunk : 0;
   tail[b] = rem;   // 0 for empty rows and for threads at or beyond n_seq
   (void)block_scan_1024(n > 0, wsum, &n_last);   // also orders the writes to tail before the reads below
@@ -227,9 +245,7 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
       rank += (t.z > rem) || (t.z == rem && o + 2 < b);
       rank += (t.w > rem) || (t.w == rem && o + 3 < b);
     }
-    const int i = total_full + rank;
-    work[1 + 2 * i] = b;
-    work[2 + 2 * i] = n - 1;
+    put(total_full + rank, n - 1);
   }
   if (b == 0) work[0] = total_full + n_last;
 }
@@ -290,11 +306,14 @@ int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx) {
   return chunk;
 }
 
-int64_t attention_worklist_ints(int n_seq, int max_chunks) { return 1 + 2 * (int64_t)n_seq * max_chunks; }
+// ints of the work buffer (which must be 32-byte aligned): a header of 8, then one 8-int record per item
+int64_t attention_worklist_ints(int n_seq, int max_chunks) { return 8 + 8 * (int64_t)n_seq * max_chunks; }
 
-int launch_attention_worklist(const int32_t *ctx_len, int32_t *work, int n_seq, int chunk, hipStream_t s) {
-  if (n_seq <= 0 || n_seq > 1024) return -1;
-  hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, s, ctx_len, work, n_seq, chunk);
+int launch_attention_worklist(const int32_t *ctx_len, const int32_t *row_slot, const int32_t *page_table, int32_t *work,
+                              int n_seq, int chunk, int page_tokens, int pages_per_seq, hipStream_t s) {
+  if (n_seq <= 0 || n_seq > 1024 || ((uintptr_t)work & 31)) return -1;
+  hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, s, ctx_len, row_slot, page_table, work, n_seq, chunk,
+                     page_tokens, pages_per_seq);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 

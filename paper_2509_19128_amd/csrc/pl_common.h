@@ -30,7 +30,7 @@ struct AttnParams {
   const int32_t *page_table;// [n_slots, pages_per_seq], row = slot_of_row[row] (or row if null)
   const int32_t *ctx_len;   // [n_seq]
   const int32_t *row_slot;  // [n_seq] or null
-  const int32_t *work;      // work list built by launch_attention_worklist for these ctx_len
+  const int32_t *work;      // work list built by launch_attention_worklist for these ctx_len, row_slot and page_table
   int32_t max_items;        // upper bound on the list length (sizes the grid)
   bf16_t *out;              // [n_seq, Hq, hd]
   float *part_o;            // [n_seq, Hkv, max_chunks, G, hd]
@@ -39,7 +39,8 @@ struct AttnParams {
 };
 int launch_attention(const AttnParams &p, hipStream_t s);
 int64_t attention_worklist_ints(int n_seq, int max_chunks);
-int launch_attention_worklist(const int32_t *ctx_len, int32_t *work, int n_seq, int chunk, hipStream_t s);
+int launch_attention_worklist(const int32_t *ctx_len, const int32_t *row_slot, const int32_t *page_table, int32_t *work,
+                              int n_seq, int chunk, int page_tokens, int pages_per_seq, hipStream_t s);
 int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx);
 
 int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,

@@ -278,7 +278,8 @@ int enqueue_step(pl_engine *e, int n, bool prefill = false) {
   const bf16_t *lm = base + e->layout.back().offset;
   int rc = 0;
   rc |= pl::launch_rope_tables(e->m_pos(true), e->cs, e->ctx_len, n, c.head_dim, c.rope_theta, s);
-  rc |= pl::launch_attention_worklist(e->ctx_len, e->attn_work, n, e->attn_chunk, s);
+  rc |= pl::launch_attention_worklist(e->ctx_len, e->m_row_slot(true), e->pt_d, e->attn_work, n, e->attn_chunk,
+                                      e->page_tokens, e->pages_per_seq, s);
   const bf16_t *g_first = c.n_layers ? layer_weights(e, 0).g1 : gf;
   rc |= pl::launch_embed_rmsnorm(embed, g_first, e->m_input(true), nullptr, e->m_row_slot(true), e->h, e->a, n,
                                  d, c.vocab, c.rms_eps, s);
@@ -891,7 +892,7 @@ int64_t pl_attention_workspace_bytes(int32_t n_seq, int32_t n_q_heads, int32_t n
   if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || hd < 1 || max_ctx < 1) return 0;
   const int chunk = pl::attention_chunk_tokens(n_seq, n_kv_heads, max_ctx);
   const int64_t max_chunks = (max_ctx + chunk - 1) / chunk;
-  return (int64_t)n_seq * n_q_heads * max_chunks * (hd + 2) * 4 + pl::attention_worklist_ints(n_seq, (int)max_chunks) * 4;
+  return (int64_t)n_seq * n_q_heads * max_chunks * (hd + 2) * 4 + pl::attention_worklist_ints(n_seq, (int)max_chunks) * 4 + 32;
 }
 
 int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page_table, const int32_t *ctx_len,
@@ -912,11 +913,11 @@ int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page
   const int64_t np = (int64_t)n_seq * n_q_heads * p.max_chunks;
   p.part_o = (float *)workspace;
   p.part_ml = p.part_o + np * hd;
-  int32_t *work = (int32_t *)(p.part_ml + np * 2);
+  int32_t *work = (int32_t *)(((uintptr_t)(p.part_ml + np * 2) + 31) & ~(uintptr_t)31);   // records are read 16 bytes at a time
   p.work = work;
   p.max_items = n_seq * p.max_chunks;
   if (n_seq > 1024) return fail(PL_E_INVAL, "at most 1024 sequences per launch");
-  if (pl::launch_attention_worklist(ctx_len, work, n_seq, p.chunk, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
+  if (pl::launch_attention_worklist(ctx_len, nullptr, page_table, work, n_seq, p.chunk, page_tokens, pages_per_seq, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
   if (pl::launch_attention(p, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
   return PL_OK;
 }
