@@ -238,7 +238,11 @@ int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, int32_t non
  *   out        device bf16 [n_seq, n_q_heads, hd]
  *   workspace  device, at least pl_attention_workspace_bytes(...) bytes
  * max_ctx bounds ctx_len (sizes the launch).  Positions at or beyond ctx_len inside the last page
- * must hold finite values. */
+ * must hold finite values.  Three launches on `stream` (work list from ctx_len and page_table, the
+ * attention proper, the merge of sequences split in chunks); the caller owns every buffer, the
+ * workspace holds nothing of value afterwards.  PL_E_INVAL (nothing launched) for n_seq outside
+ * [1, 1024], head_dim not in {32, 64, 128}, more than 16 query heads per kv head, page_tokens not a
+ * multiple of 32, or max_ctx beyond pages_per_seq * page_tokens. */
 int64_t pl_attention_workspace_bytes(int32_t n_seq, int32_t n_q_heads, int32_t n_kv_heads, int32_t hd,
                                      int32_t max_ctx);
 int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page_table,
