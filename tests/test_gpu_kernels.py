@@ -131,6 +131,26 @@ def test_attention_chunk_boundaries_in_the_benchmark_launch_shape():
         assert ok, (b, int(ctx[b]), err)
 
 
+def test_attention_of_a_sequence_does_not_depend_on_its_neighbours():
+    """The chunk length is a function of the launch shape only, and the merge order is fixed: the same
+    sequence gives bit-identical output whatever the other rows' contexts are and wherever it sits in
+    the work list (which is sorted by length)."""
+    rng = np.random.default_rng(321)
+    Hq, Hkv, hd, pt, n = 28, 4, 128, 128, 64
+    ctx_a = rng.integers(100, 12000, n).astype(np.int32)
+    ctx_b = rng.integers(100, 12000, n).astype(np.int32)
+    keep = [3, 17, 40]
+    ctx_a[keep] = ctx_b[keep] = [9000, 700, 16896]
+    both = np.maximum(ctx_a, ctx_b)
+    pool, table, pps, _ = _paged_inputs(rng, both, Hq, Hkv, hd, pt, [])
+    q = synth.bf16_round(rng.standard_normal((n, Hq, hd)).astype(np.float32))
+    out_a = _run_attention(q, pool, table, ctx_a, Hq, Hkv, hd, pt, pps, 16896)
+    out_b = _run_attention(q, pool, table, ctx_b, Hq, Hkv, hd, pt, pps, 16896)
+    for b in keep:
+        assert np.array_equal(out_a[b], out_b[b]), b
+    assert not np.array_equal(out_a[0], out_b[0])        # the other rows did change
+
+
 def test_attention_rejects_bad_arguments():
     t = torch.zeros(1 << 16, device="cuda", dtype=torch.bfloat16)
     p = t.data_ptr()
