@@ -31,10 +31,12 @@ WORKLOADS = {
     "7b": dict(model="7b", batch=256, prompt=512, mean=4096.0, gmax=16384, swap_every=128, pool_tokens=1_700_000),
     "1p5b": dict(model="1p5b", batch=64, prompt=256, mean=2048.0, gmax=8192, swap_every=256, pool_tokens=400_000),
     "tiny": dict(model="tiny", batch=4, prompt=16, mean=48.0, gmax=64, swap_every=32, pool_tokens=4 * 128),
-    # 32B shape: two 65.5 GB weight buffers + 256 KiB of KV per token; batch 64 is what fits 288 GB with headroom
-    # (the configuration asks for 128 "or the largest that fits"); total length lognormal(mean 6000), at most 16384
-    "32b": dict(model="32b", batch=64, prompt=512, mean=5488.0, gmax=15872, swap_every=64, pool_tokens=400_000,
-                host_staged=True),
+    # 32B shape: two 65.5 GB weight buffers + 256 KiB of KV per token.  128 slots as the configuration asks; the
+    # KV pool takes what is left of the 288 GB (pool_tokens = 0), which holds fewer tokens than 128 sequences at
+    # the stationary context mix need, so refill is under admission control (see Workload.refill) and the batch
+    # actually achieved is reported; total length lognormal(mean 6000), at most 16384
+    "32b": dict(model="32b", batch=128, prompt=512, mean=5488.0, gmax=15872, swap_every=64, pool_tokens=0,
+                host_staged=True, admission=True),
 }
 
 
@@ -114,6 +116,16 @@ class Workload:
         self.keep_history = keep_history
         self.rng = np.random.default_rng(seed)
         self.next_id = 0
+        self.page_tokens = eng.cfg.kv_page_tokens or 128
+        self.preempted = 0
+        self.order = []                              # occupied slots, oldest admission first
+
+    def preempt_youngest(self):
+        """The pool ran dry although admission kept headroom: retire the sequence admitted last (it has
+        the least work to lose).  Its tokens so far are dropped; counted in `preempted`."""
+        slot = self.order.pop()
+        self.eng.retire_sequence(slot)
+        self.preempted += 1
 
     def _new_len(self):
         return int(synth.lognormal_lengths(self.rng, 1, self.spec["mean"], 1, self.spec["gmax"])[0])
@@ -130,29 +142,53 @@ class Workload:
         for i in range(B):
             G = int(g[i])
             pos = int(self.rng.integers(first, P + G - 1))
+            if not self._headroom_ok(pos + 1):
+                break                                # the pool holds no more sequences at these ages
             prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
             slot = self.eng.debug_add_sequence_at(self.next_id, prompt, P, G, 1.0, pos, max(0, pos - (P - 1)),
                                                   int(self.rng.integers(0, self.model.vocab)))
+            self.order.append(slot)
             if self.keep_history:   # tokens "read so far", so that the cache can be recomputed after an update
                 hist = np.concatenate([prompt, self.rng.integers(0, self.model.vocab, max(0, pos - P))])[:pos]
                 self.eng.debug_set_history(slot, hist)
             self.next_id += 1
 
+    def _headroom_ok(self, extra_tokens):
+        """Admission control for pools smaller than the batch's worst case: a sequence is admitted only if,
+        after its prompt, the free pages still cover one more page for every sequence in flight plus a tenth
+        of the pool (sequences keep growing; running dry would force a preemption)."""
+        if not self.spec.get("admission"):
+            return True
+        st = self.eng.stats()
+        page = self.page_tokens
+        need = (extra_tokens + page - 1) // page + self.eng.num_active() + 1 + st["kv_pages_total"] // 10
+        return st["kv_pages_free"] >= need
+
     def refill(self):
         P = self.spec["prompt"]
-        while self.eng.num_active() < self.spec["batch"]:
+        while self.eng.num_active() < self.spec["batch"] and self._headroom_ok(P):
             prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
             slot = self.eng.add_sequence(self.next_id, prompt, self._new_len(), 1.0)
+            self.order.append(slot)
             if self.batched_prefill:
                 self.eng.prefill(slot)
             self.next_id += 1
 
     def step(self):
-        out = self.eng.decode_step()
+        try:
+            out = self.eng.decode_step()
+        except Exception as ex:                      # pool exhausted in spite of the headroom: preempt the youngest
+            if getattr(ex, "code", None) != -3:
+                raise
+            self.preempt_youngest()
+            out = self.eng.decode_step()
+        if self.spec.get("admission") and self.eng.num_active() < self.spec["batch"]:
+            self.refill()                            # pages freed earlier may admit a waiting sequence now
         fin = np.nonzero(out["finished"])[0]
         emitted = int(out["emitted"].sum())
         for i in fin:
             self.eng.retire_sequence(int(out["slot"][i]))
+            self.order.remove(int(out["slot"][i]))
         if len(fin):
             self.refill()
         return emitted, out["step_ms"], out["swap_stall_ms"], out["weight_version"][0] if out["n"] else 0
@@ -173,6 +209,58 @@ def stream_ceiling(torch, pl, nontemporal=False):
         torch.cuda.synchronize()
         best = max(best, n / (a.elapsed_time(b) * 1e-3) / 1e9)
     return best
+
+
+PROFILE_OF = {"7b": "decode_step_7b_b256.md", "32b": "decode_step_32b_b64.md"}
+
+
+def counter_traffic(workload, algorithmic_bytes):
+    """HBM bytes one attention launch moved according to rocprofv3's counters: the committed summary of
+    the counter runs states them as a multiple of the algorithmic bytes (a line `attn_traffic_ratio: x`);
+    None where no such run was recorded."""
+    path = os.path.join(ROOT, "profiles", PROFILE_OF.get(workload, ""))
+    try:
+        for line in open(path):
+            if line.startswith("attn_traffic_ratio:"):
+                return float(line.split(":")[1].split()[0]) * algorithmic_bytes
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline_tiny():
+    """The tiny configuration is small enough for the oracle to run the WHOLE workload: batch 4, 16-token
+    prompts, 64 generated tokens each (4 x (16 + 64 - 1) slot-steps), one weight update landing at
+    generated token 32, cache kept.  Timed on one thread and again with the BLAS library's default
+    threads; generated tokens per second."""
+    import threadpoolctl
+    from oracle.engine import OracleEngine
+    m = synth.CONFIGS["tiny"]
+    master = synth.make_weights(m, seed=1235)
+    w = [{k: synth.bf16_round(v).astype(np.float64) for k, v in ws.items()}
+         for ws in (master, synth.perturb_weights(master, seed=1236))]
+    prompts = synth.random_prompts(np.random.default_rng(77), 4, 16, m.vocab)
+
+    def run():
+        orc = OracleEngine(m, w[0], max_batch=4, seed=1)
+        for i in range(4):
+            orc.add_sequence(i, prompts[i], 64)
+        t0 = time.perf_counter()
+        emitted = 0
+        for step in range(16 + 64 - 1):
+            if step == 15 + 32:
+                orc.swap_weights(w[1])
+            emitted += sum(r.emitted for r in orc.decode_step())
+        return emitted / (time.perf_counter() - t0)
+
+    with threadpoolctl.threadpool_limits(1):
+        single = run()
+    multi = run()
+    cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
+    return {"value": single, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": "the whole tiny workload: 4 sequences x (16 prompt + 64 generated tokens), update at generated "
+                      "token 32, float64, one thread",
+            "all_cores": {"value": multi, "cores": int(cores)}}
 
 
 def cpu_baseline(model, seconds_budget=20.0):
@@ -475,24 +563,40 @@ def main():
     wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill=args.prefill == "batched", keep_history=args.recompute_kv)
     wl.admit_steady_state()
     eng.debug_set_profile(0 if args.no_profile else 1)   # events around the attention launches only
+    step_ms, stalls, flips, requests = [], [], [], []
+    swaps_requested = 0
+
+    def request_update(k):
+        """Alg. 2: the trainer requests an update; the engine stages it while decoding goes on."""
+        nonlocal swaps_requested
+        try:
+            eng.swap_weights(host[swaps_requested % 2].data_ptr(), eng.weight_nbytes(),
+                             flags=pl.PL_SWAP_ASYNC | (pl.PL_SWAP_RECOMPUTE_KV if args.recompute_kv else 0))
+            swaps_requested += 1
+            requests.append(k)
+        except pl.PlError as ex:
+            if ex.code != pl.PL_E_BUSY:
+                raise
+
+    # Updates arrive every `swap_every` steps; where that cycle stands when the timed window opens is
+    # arbitrary.  A window of at least one period takes the first request half a period in.  A shorter
+    # window would otherwise contain no update at all, so its request is issued when the warm-up starts:
+    # the staging copy is then in flight over the first timed steps and the flip falls inside the window
+    # (this charges the window one update per `steps` instead of one per `swap_every`).
+    every = spec["swap_every"]
+    short_window = bool(every) and args.steps < every
+    if short_window:
+        request_update(-args.warmup)
     for _ in range(args.warmup):
         wl.step()
     torch.cuda.synchronize()
     s0 = eng.stats()
     emitted = 0
-    step_ms, stalls, flips, requests = [], [], [], []
-    swaps_requested = 0
     last_version = s0["active_version"]
     t0 = time.perf_counter()
     for k in range(args.steps):
-        if spec["swap_every"] and k % spec["swap_every"] == spec["swap_every"] // 2:
-            try:    # Alg. 2: the trainer requests an update; the engine stages it while decoding goes on
-                eng.swap_weights(host[swaps_requested % 2].data_ptr(), eng.weight_nbytes(), flags=pl.PL_SWAP_ASYNC | (pl.PL_SWAP_RECOMPUTE_KV if args.recompute_kv else 0))
-                swaps_requested += 1
-                requests.append(k)
-            except pl.PlError as ex:
-                if ex.code != pl.PL_E_BUSY:
-                    raise
+        if every and not short_window and k % every == every // 2:
+            request_update(k)
         e, ms, stall, ver = wl.step()
         emitted += e
         step_ms.append(ms)
@@ -519,19 +623,20 @@ def main():
                                      "attn_ms", "gemm_ms", "sample_ms", "other_ms", "attn_launches", "attn_kv_bytes")}
     sm = np.asarray(step_ms)
     med = float(np.median(sm))
-    # swap stall: the step that contains the flip against the median of the 16 surrounding steps
-    stall_ms = 0.0
+    # swap stall: the step that contains the flip against the median of the 16 surrounding steps (None if no
+    # flip fell inside the timed window: nothing was measured then)
+    stall_ms = None
     for k in flips:
         lo, hi = max(0, k - 8), min(len(sm), k + 9)
         around = np.concatenate([sm[lo:k], sm[k + 1:hi]])
         if len(around):
-            stall_ms = max(stall_ms, float(sm[k] - np.median(around)) + float(stalls[k]))
+            stall_ms = max(stall_ms or 0.0, float(sm[k] - np.median(around)) + float(stalls[k]))
     # interference: decode steps that run while a staging copy is in flight (request .. flip) against the rest
     during = np.zeros(len(sm), bool)
     for rq in requests:
         fl = [f for f in flips if f >= rq]
-        during[rq:(fl[0] if fl else len(sm))] = True
-    interference = float(sm[during].mean() - sm[~during].mean()) if during.any() and (~during).any() else 0.0
+        during[max(rq, 0):(fl[0] if fl else len(sm))] = True
+    interference = float(sm[during].mean() - sm[~during].mean()) if during.any() and (~during).any() else None
     res = {
         "metric": "generated tokens/s/GPU at constant batch", "value": emitted / wall, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps,
@@ -542,12 +647,15 @@ def main():
                                f"prompts read {'in batched passes at admission' if args.prefill == 'batched' else 'one token per step'}",
                    "mean_context": d["algorithmic_bytes"] and float((d["attn_kv_bytes"] / max(d["attn_launches"], 1)) /
                                                                     (4.0 * model.n_kv_heads * model.head_dim) / spec["batch"]),
-                   "slot_utilisation": d["tokens_emitted"] / max(d["slot_steps"], 1)},
+                   "slot_utilisation": d["tokens_emitted"] / max(d["slot_steps"], 1),
+                   "mean_batch": d["slot_steps"] / max(d["steps"], 1), "preempted": wl.preempted,
+                   "kv_pool_tokens": s1["kv_pages_total"] * wl.page_tokens},
         "gpu_ms_per_step_median": med, "gpu_ms_per_step_p99": float(np.percentile(sm, 99)),
         "step_hbm": {"algorithmic_bytes_per_step": d["algorithmic_bytes"] / max(d["steps"], 1),
                      "achieved_GBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6,
                      "frac_of_8TBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6 / HBM_PEAK_GBS},
-        "swap": {"requested": swaps_requested, "flips_at_steps": flips, "stall_ms": stall_ms,
+        "swap": {"requested": swaps_requested, "requested_at_steps": requests, "flips_at_steps": flips,
+                 "window_contains_a_flip": bool(flips), "stall_ms": stall_ms,
                  "steps_overlapping_a_copy": int(during.sum()), "interference_ms_per_overlapping_step": interference,
                  "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9,
                  "kv_cache": "recomputed at the flip" if args.recompute_kv else "kept",
@@ -566,9 +674,9 @@ def main():
         ach = per_launch_bytes / per_launch_ms / 1e6
         res["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel (+ merge)", "achieved": ach, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                           # rocprofv3 FETCH_SIZE (x2.0, calibrated on plain copies) + WRITE_SIZE per launch came to
-                           # 1.01 x the algorithmic bytes on this workload (profiles/decode_step_7b_b256.md)
-                           "traffic": 1.01 * per_launch_bytes if args.workload == "7b" else None,
+                           # HBM bytes per launch from the rocprofv3 counter runs of this same command
+                           # (FETCH_SIZE and WRITE_SIZE, scaled on plain copies), as recorded in profiles/
+                           "traffic": counter_traffic(args.workload, per_launch_bytes),
                            "bytes_per_launch": per_launch_bytes, "ms_per_launch": per_launch_ms}
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -577,7 +685,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(model)
+        res["cpu_baseline"] = cpu_baseline_tiny() if args.workload == "tiny" else cpu_baseline(model)
     eng.close()
     print(json.dumps(res))
 

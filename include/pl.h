@@ -56,7 +56,9 @@ typedef struct {
   float rms_eps;    /* added to the mean square inside the root, e.g. 1e-6 */
   int32_t max_batch;      /* H of Alg. 2: number of slots */
   int32_t max_context;    /* cap on prompt + generated positions of one sequence */
-  int64_t kv_pool_tokens; /* capacity of the paged KV pool, in token positions (all layers) */
+  int64_t kv_pool_tokens; /* capacity of the paged KV pool, in token positions (all layers); 0 = what is
+                             left of the device memory after the weights and work buffers, minus a
+                             6 GiB reserve for the caller, at most max_batch * max_context */
   int32_t kv_page_tokens; /* tokens per page: multiple of 32; 0 selects 128 */
   int32_t n_weight_buffers; /* 2: in-flight updates are staged into the inactive buffer; 1: updates
                                overwrite the only buffer and always block */
@@ -108,7 +110,8 @@ typedef struct {
 
 /* Create an engine: allocates weight buffer(s), the KV page pool and work buffers on cfg->device.
  * PL_E_INVAL if a shape is unsupported (head_dim not in {32, 64, 128}, n_q_heads not a multiple
- * of n_kv_heads or group > 16, d_model, d_ffn or n_q_heads*head_dim not a multiple of 256, ...). */
+ * of n_kv_heads or group > 16, d_model, d_ffn or n_q_heads*head_dim not a multiple of 256, a weight
+ * matrix of 2 GiB or more, ...); PL_E_NOMEM if an allocation fails (nothing is leaked). */
 int pl_create(const pl_model_cfg *cfg, pl_engine **out);
 void pl_destroy(pl_engine *e);
 const char *pl_last_error(void);
@@ -130,6 +133,15 @@ int32_t pl_weight_count(const pl_engine *e);
 int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t *offset_elems,
                      int64_t shape[2]);
 int64_t pl_weight_nbytes(const pl_engine *e);
+
+/* Host helper (layout only, no device access): write one source tensor into its place in a host
+ * image `blob` (pl_weight_nbytes bytes) of the flat blob described above.  `name` is "embed", "gf",
+ * "lm_head", or "l<l>.<t>" with t one of g1, g2 (gains, [d]), wq [Hq hd, d], wk, wv [Hkv hd, d],
+ * wo [d, Hq hd], wg, wu [F, d], wd [d, F]; `src` is the tensor row-major [out_features, in_features],
+ * fp32 if src_is_f32 (rounded to bf16, nearest even) or bf16 bit patterns otherwise.  The row
+ * concatenation q|k|v, the 32-row gate/up interleave and the operand ordering are applied here, so a
+ * caller never needs the formulas.  PL_E_INVAL for an unknown name. */
+int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32_t src_is_f32, void *blob);
 
 /* Blocking load of version 0 (or a blocking replacement of the active buffer, version + 1, if
  * weights are already loaded).  src: host or device pointer to pl_weight_nbytes bytes. */
@@ -214,6 +226,10 @@ int pl_debug_set_history(pl_engine *e, int32_t slot, const int32_t *tokens, int3
  * else lands in other_ms); 2 around every group (attention, GEMMs, sampler, rest).  Each event costs a
  * little GPU time between kernels, which is why level 1 exists. */
 int pl_debug_set_profile(pl_engine *e, int32_t level);
+/* Debugging aid for the double-buffered update: when on, the step that flips to the new weights
+ * first fills the buffer that just went inactive with bf16 NaN, so any kernel that still reads the
+ * old weights after the flip shows up as NaN logits.  Costs one fill of the blob per update. */
+int pl_debug_set_poison(pl_engine *e, int32_t on);
 /* Device pointer and size of the KV page pool (to fill it with synthetic values). */
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 
@@ -238,8 +254,8 @@ int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, int32_t non
  *   out        device bf16 [n_seq, n_q_heads, hd]
  *   workspace  device, at least pl_attention_workspace_bytes(...) bytes
  * max_ctx bounds ctx_len (sizes the launch).  Positions at or beyond ctx_len inside the last page
- * must hold finite values.  Three launches on `stream` (work list from ctx_len and page_table, the
- * attention proper, the merge of sequences split in chunks); the caller owns every buffer, the
+ * must hold finite values.  Up to three launches on `stream` (work list from ctx_len and page_table, the
+ * attention proper, and, when max_ctx allows sequences of several chunks, their merge); the caller owns every buffer, the
  * workspace holds nothing of value afterwards.  PL_E_INVAL (nothing launched) for n_seq outside
  * [1, 1024], head_dim not in {32, 64, 128}, more than 16 query heads per kv head, page_tokens not a
  * multiple of 32, or max_ctx beyond pages_per_seq * page_tokens. */
@@ -257,7 +273,8 @@ int pl_kv_pack_host(uint16_t *pages_host, const int32_t *page_ids, const float *
 
 /* y = x W^T with bf16 inputs and fp32 accumulation.  x device bf16 [M, K] row-major; w device bf16
  * [N, K] in MFMA operand order (see pl_weight_layout); K a multiple of 256, N a multiple of 32,
- * 1 <= M <= 512.
+ * 1 <= M <= 512, and both x and w below 2 GiB (PL_E_INVAL otherwise: the kernels address an operand
+ * through one 32-bit buffer descriptor).
  *   mode 0: y device fp32 [splits, M, N]; slice s holds the partial sum over columns
  *           [256 s c, min(256 (s + 1) c, K)), c = ceil((K / 256) / splits); their sum over s is the
  *           product.  1 <= splits <= K / 256 and no slice may be empty.

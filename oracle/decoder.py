@@ -71,10 +71,9 @@ class Cache:
         return c
 
 
-def step(cfg, W, token, pos, cache, dtype=np.float64, kv_round=None):
+def step(cfg, W, token, pos, cache, dtype=np.float64):
     """Logits [vocab] for input `token` at position `pos` (== len(cache)); appends this
-    position's rotated key and value to `cache`.  `kv_round`, if given, is applied to k and v
-    before they are stored and attended (models a cache that stores fewer bits)."""
+    position's rotated key and value to `cache`."""
     assert pos == len(cache) or cfg.n_layers == 0
     w = lambda n: W[n].astype(dtype, copy=False)
     h = w("embed")[token].copy()
@@ -85,8 +84,6 @@ def step(cfg, W, token, pos, cache, dtype=np.float64, kv_round=None):
         v = (w(f"l{l}.wv") @ a).reshape(cfg.n_kv_heads, cfg.head_dim)
         q = rope(q, pos, cfg.rope_theta)
         k = rope(k, pos, cfg.rope_theta)
-        if kv_round is not None:
-            k, v = kv_round(k).astype(dtype), kv_round(v).astype(dtype)
         cache.k[l] = np.concatenate([cache.k[l], k[None]], axis=0)
         cache.v[l] = np.concatenate([cache.v[l], v[None]], axis=0)
         o = attend_one(q, cache.k[l], cache.v[l]).reshape(-1)

@@ -45,9 +45,9 @@ class _Seq:
 
 
 class OracleEngine:
-    def __init__(self, cfg, weights, max_batch, seed, dtype=np.float64, kv_round=None):
+    def __init__(self, cfg, weights, max_batch, seed, dtype=np.float64):
         self.cfg, self.W, self.H, self.seed = cfg, weights, max_batch, seed
-        self.dtype, self.kv_round = dtype, kv_round
+        self.dtype = dtype
         self.slots = [None] * max_batch
         self.version = 0
         self.last_logits = {}
@@ -85,7 +85,7 @@ class OracleEngine:
                     continue
                 seq.cache = decoder.Cache(self.cfg, self.dtype)
                 for p, tok in enumerate(seq.inputs):
-                    decoder.step(self.cfg, self.W, tok, p, seq.cache, self.dtype, self.kv_round)
+                    decoder.step(self.cfg, self.W, tok, p, seq.cache, self.dtype)
         return self.version
 
     # -- Alg. 2: "generate next tokens with mu" -----------------------------------------------
@@ -99,7 +99,7 @@ class OracleEngine:
             p = seq.pos
             n = len(seq.prompt)
             x = int(seq.prompt[p]) if p < n else seq.last_token
-            logits = decoder.step(self.cfg, self.W, x, p, seq.cache, self.dtype, self.kv_round)
+            logits = decoder.step(self.cfg, self.W, x, p, seq.cache, self.dtype)
             logits = logits.astype(np.float32)
             self.last_logits[s] = logits
             f = -1 if forced is None else int(forced[s])

@@ -20,9 +20,9 @@ PL_DEVICE_NONE = -1
 # every symbol include/pl.h declares
 EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
-    "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_retire_sequence",
+    "pl_pack_weights", "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
-    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
+    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample", "pl_is_ess",
 ]
 
@@ -86,6 +86,7 @@ def lib():
         "pl_weight_count": (i32, [vp]),
         "pl_weight_layout": (C.c_int, [vp, i32, P(C.c_char_p), P(i64), P(i64)]),
         "pl_weight_nbytes": (i64, [vp]),
+        "pl_pack_weights": (C.c_int, [vp, C.c_char_p, vp, i32, vp]),
         "pl_load_weights": (C.c_int, [vp, vp, i64]),
         "pl_swap_weights": (C.c_int, [vp, vp, i64, u32, P(u32)]),
         "pl_swap_poll": (C.c_int, [vp, P(i32), P(u32)]),
@@ -102,6 +103,7 @@ def lib():
         "pl_debug_add_sequence_at": (C.c_int, [vp, u64, vp, i32, i32, f32, i32, i32, i32, P(i32)]),
         "pl_debug_kv_pool": (C.c_int, [vp, P(vp), P(i64)]),
         "pl_debug_set_profile": (C.c_int, [vp, i32]),
+        "pl_debug_set_poison": (C.c_int, [vp, i32]),
         "pl_debug_stream_read": (i64, [vp, i64, i32, vp]),
         "pl_attention_workspace_bytes": (i64, [i32, i32, i32, i32, i32]),
         "pl_attention_decode": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
@@ -205,6 +207,14 @@ class Engine:
             assert src.size == r * c, (name, src.shape, r, c)
             bits = to_bits(np.ascontiguousarray(src, np.float32)).reshape(src.shape)
             blob[off:off + r * c] = bits.reshape(-1) if (c == 1 or name == "embed") else operand_order(bits)
+        return blob
+
+    def pack_weights_c(self, tensors):
+        """The same blob through the library's host helper pl_pack_weights (fp32 sources)."""
+        blob = np.zeros(self.weight_nbytes() // 2, np.uint16)
+        for name, w in tensors.items():
+            w = np.ascontiguousarray(w, np.float32)
+            _check(lib().pl_pack_weights(self._h, name.encode(), _np_ptr(w), 1, _np_ptr(blob)))
         return blob
 
     def unpack_weights(self, blob, from_bits, names=None):
@@ -321,6 +331,9 @@ class Engine:
 
     def debug_set_profile(self, level):
         _check(lib().pl_debug_set_profile(self._h, int(level)))
+
+    def debug_set_poison(self, on):
+        _check(lib().pl_debug_set_poison(self._h, int(bool(on))))
 
     def debug_kv_pool(self):
         p, n = C.c_void_p(), C.c_int64()

@@ -205,13 +205,14 @@ __device__ inline int block_scan_1024(int v, int *wsum, int *total) {
   return v + before;
 }
 
-// work[0] = number of items; the items are 8-int records from work[8] on: {sequence, chunk, context
-// length, slot, ids of the chunk's first four pages}.  All full chunks come first, then each
+// work[0] = number of items, work[1] = number of sequences longer than one chunk (listed in `multi`);
+// the items are 8-int records from work[8] on: {sequence, chunk, context length, slot, ids of the
+// chunk's first four pages}.  All full chunks come first, then each
 // sequence's last (partial or full) chunk, longest first, so that the workgroups still running when
 // the grid drains are the short ones.  One workgroup; n_seq <= 1024.
 __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_len, const int32_t *row_slot,
-                                                             const int32_t *page_table, int32_t *work, int n_seq,
-                                                             int chunk, int page_tokens, int pages_per_seq) {
+                                                             const int32_t *page_table, int32_t *work, int32_t *multi,
+                                                             int n_seq, int chunk, int page_tokens, int pages_per_seq) {
   __shared__ int wsum[16];
   __shared__ __attribute__((aligned(16))) int tail[1024];
   const int b = threadIdx.x;
@@ -247,16 +248,20 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
     }
     put(total_full + rank, n - 1);
   }
-  if (b == 0) work[0] = total_full + n_last;
+  // rows that span several chunks, in row order: what the merge kernel walks
+  int n_multi;
+  const int mi = block_scan_1024(n > 1, wsum, &n_multi) - (n > 1);
+  if (n > 1) multi[mi] = b;
+  if (b == 0) { work[0] = total_full + n_last; work[1] = n_multi; }
 }
 
-// Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup per (sequence, kv
-// head); most sequences fit one chunk and their workgroups leave at once.
+// Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup per (listed sequence,
+// kv head); the list is the work-list kernel's, the grid is sized by the caller's bound on its length.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
-  const int b = blockIdx.y, g = blockIdx.x;
+  if ((int)blockIdx.y >= p.work[1]) return;
+  const int b = p.multi[blockIdx.y], g = blockIdx.x;
   const int ctx = p.ctx_len[b];
-  if (ctx <= p.chunk) return;   // empty rows and single-chunk rows were written by the first kernel
   const int G = p.Hq / p.Hkv;
   const int nchunk = (ctx + p.chunk - 1) / p.chunk;
   const int64_t base = ((int64_t)b * p.Hkv + g) * p.max_chunks;
@@ -306,33 +311,39 @@ int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx) {
   return chunk;
 }
 
-// ints of the work buffer (which must be 32-byte aligned): a header of 8, then one 8-int record per item
-int64_t attention_worklist_ints(int n_seq, int max_chunks) { return 8 + 8 * (int64_t)n_seq * max_chunks; }
+// ints of the work buffer (which must be 32-byte aligned): a header of 8, one 8-int record per item,
+// then the list of multi-chunk sequences
+int64_t attention_worklist_ints(int n_seq, int max_chunks) { return 8 + 8 * (int64_t)n_seq * max_chunks + n_seq; }
+const int32_t *attention_multi_list(const int32_t *work, int n_seq, int max_chunks) {
+  return work + 8 + 8 * (int64_t)n_seq * max_chunks;
+}
 
 int launch_attention_worklist(const int32_t *ctx_len, const int32_t *row_slot, const int32_t *page_table, int32_t *work,
-                              int n_seq, int chunk, int page_tokens, int pages_per_seq, hipStream_t s) {
+                              int n_seq, int max_chunks, int chunk, int page_tokens, int pages_per_seq, hipStream_t s) {
   if (n_seq <= 0 || n_seq > 1024 || ((uintptr_t)work & 31)) return -1;
-  hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, s, ctx_len, row_slot, page_table, work, n_seq, chunk,
-                     page_tokens, pages_per_seq);
+  hipLaunchKernelGGL(attn_worklist_kernel, dim3(1), dim3(1024), 0, s, ctx_len, row_slot, page_table, work,
+                     (int32_t *)attention_multi_list(work, n_seq, max_chunks), n_seq, chunk, page_tokens, pages_per_seq);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
 int launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_seq <= 0) return 0;
-  // max_items bounds the list (the host knows the longest context of the step, or uses max_chunks)
-  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hkv, p.n_seq);
+  // max_items and max_multi bound the two lists (a host that knows the step's contexts passes the
+  // exact lengths; otherwise n_seq * max_chunks and n_seq)
+  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hkv, p.max_multi > 0 ? p.max_multi : 1);
+  const bool merge = p.max_multi > 0;
   switch (p.hd) {
     case 128:
       hipLaunchKernelGGL((attn_decode_kernel<128, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(256), 0, s, p);
+      if (merge) hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(256), 0, s, p);
       break;
     case 64:
       hipLaunchKernelGGL((attn_decode_kernel<64, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(256), 0, s, p);
+      if (merge) hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(256), 0, s, p);
       break;
     case 32:
       hipLaunchKernelGGL((attn_decode_kernel<32, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(256), 0, s, p);
+      if (merge) hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(256), 0, s, p);
       break;
     default:
       return -1;

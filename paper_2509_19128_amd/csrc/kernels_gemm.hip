@@ -261,6 +261,8 @@ int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, 
   if ((splits - 1) * ((K / (4 * BK) + splits - 1) / splits) >= K / (4 * BK)) return -1;   // an empty slice
   if (mode == 1 && (splits != 1 || N % 64)) return -1;
   if (mode != 0 && mode != 1) return -1;
+  // beyond this the descriptor's size field and the 32-bit offsets wrap and loads read zeros
+  if ((int64_t)N * K * 2 >= GEMM_MAX_OPERAND_BYTES || (int64_t)M * K * 2 >= GEMM_MAX_OPERAND_BYTES) return -1;
   if (M <= 32) return launch_cfg<1, 4, 1, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
   if (M <= 64) return launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
   if (M <= 128) return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);

@@ -31,7 +31,9 @@ struct AttnParams {
   const int32_t *ctx_len;   // [n_seq]
   const int32_t *row_slot;  // [n_seq] or null
   const int32_t *work;      // work list built by launch_attention_worklist for these ctx_len, row_slot and page_table
+  const int32_t *multi;     // attention_multi_list(work, ...): rows longer than one chunk
   int32_t max_items;        // upper bound on the list length (sizes the grid)
+  int32_t max_multi;        // upper bound on the number of rows longer than one chunk; 0 = none, no merge launch
   bf16_t *out;              // [n_seq, Hq, hd]
   float *part_o;            // [n_seq, Hkv, max_chunks, G, hd]
   float *part_ml;           // [n_seq, Hkv, max_chunks, G, 2]
@@ -39,10 +41,14 @@ struct AttnParams {
 };
 int launch_attention(const AttnParams &p, hipStream_t s);
 int64_t attention_worklist_ints(int n_seq, int max_chunks);
+const int32_t *attention_multi_list(const int32_t *work, int n_seq, int max_chunks);
 int launch_attention_worklist(const int32_t *ctx_len, const int32_t *row_slot, const int32_t *page_table, int32_t *work,
-                              int n_seq, int chunk, int page_tokens, int pages_per_seq, hipStream_t s);
+                              int n_seq, int max_chunks, int chunk, int page_tokens, int pages_per_seq, hipStream_t s);
 int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx);
 
+// x and W are each addressed through one buffer descriptor with 32-bit byte offsets kept in signed
+// registers: an operand must stay below 2 GiB (launch_gemm returns -1 beyond that).
+constexpr int64_t GEMM_MAX_OPERAND_BYTES = (int64_t)1 << 31;
 int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,
                 hipStream_t s);
 int gemm_pick_splits(int M, int N, int K);

@@ -8,6 +8,7 @@
 #include "../../include/pl.h"
 #include "pl_common.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -98,6 +99,7 @@ struct pl_engine {
   bf16_t *a = nullptr, *q_rot = nullptr, *attn_out = nullptr, *mid = nullptr;
   int32_t *ctx_len = nullptr, *tok_d = nullptr, *attn_work = nullptr;
   int attn_items = 0;   // bound on this step's attention work items
+  int attn_multi = 0;   // rows of this step that span more than one attention chunk
   float *lp_d = nullptr;
   void *samp_ws = nullptr;
   int32_t *tok_h = nullptr;
@@ -107,6 +109,7 @@ struct pl_engine {
   hipStream_t s_dec = nullptr, s_copy = nullptr;
   hipEvent_t ev_a = nullptr, ev_b = nullptr, ev_c = nullptr;
   // optional per-kernel-group timing: events[i] closes a segment of category cats[i]
+  bool poison_inactive = false;   // debugging aid: after a flip, fill the buffer that went inactive with NaN
   int profile = 0;   // 0 off, 1 events around the attention launches only, 2 around every kernel group
   std::vector<hipEvent_t> prof_ev;
   std::vector<int> prof_cat;
@@ -117,12 +120,13 @@ struct pl_engine {
   pl_stats st{};
   int64_t streamed_weight_bytes = 0;
 
-  int32_t *m_row_slot(bool dev) { return (int32_t *)(dev ? meta_d : meta_h); }
+  // the 8-byte ids come first, so every array is aligned for its type whatever rows_cap is
+  uint64_t *m_seq_id(bool dev) { return (uint64_t *)(dev ? meta_d : meta_h); }
+  int32_t *m_row_slot(bool dev) { return (int32_t *)(m_seq_id(dev) + rows_cap); }
   int32_t *m_pos(bool dev) { return m_row_slot(dev) + rows_cap; }
   int32_t *m_input(bool dev) { return m_pos(dev) + rows_cap; }
   int32_t *m_forced(bool dev) { return m_input(dev) + rows_cap; }
   float *m_inv_t(bool dev) { return (float *)(m_forced(dev) + rows_cap); }
-  uint64_t *m_seq_id(bool dev) { return (uint64_t *)(m_inv_t(dev) + rows_cap); }
 
   const bf16_t *wptr(int buf, const char *name) const {
     for (auto &t : layout)
@@ -171,7 +175,26 @@ int check_cfg(const pl_model_cfg &c) {
   if (c.kv_page_tokens < 0 || c.kv_page_tokens % 32) return fail(PL_E_INVAL, "kv_page_tokens must be a multiple of 32");
   if (c.n_weight_buffers != 1 && c.n_weight_buffers != 2) return fail(PL_E_INVAL, "n_weight_buffers must be 1 or 2");
   if (!(c.rope_theta > 0) || !(c.rms_eps >= 0)) return fail(PL_E_INVAL, "bad rope_theta / rms_eps");
+  if (c.kv_pool_tokens < 0) return fail(PL_E_INVAL, "kv_pool_tokens must be >= 0 (0 = size the pool from free memory)");
+  // the GEMM kernels address a matrix through one 32-bit buffer descriptor
+  const int64_t qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
+  const int64_t biggest = std::max(std::max((int64_t)c.vocab, 2 * (int64_t)c.d_ffn), qd + 2 * kvd) * c.d_model;
+  if (biggest * 2 >= pl::GEMM_MAX_OPERAND_BYTES || (int64_t)c.d_model * std::max(qd, (int64_t)c.d_ffn) * 2 >= pl::GEMM_MAX_OPERAND_BYTES)
+    return fail(PL_E_INVAL, "a weight matrix would reach %lld bytes; the GEMM kernels address at most 2 GiB per matrix",
+                (long long)(biggest * 2));
   return PL_OK;
+}
+
+// device memory an automatically sized KV pool leaves to the caller
+constexpr int64_t KV_AUTO_RESERVE_BYTES = (int64_t)6 << 30;
+
+void set_pool_pages(pl_engine *e, int64_t n_pages) {
+  e->n_pages = n_pages;
+  e->layer_stride = e->page_stride * n_pages;
+  e->free_pages.clear();
+  e->free_pages.reserve(n_pages);
+  for (int64_t p = n_pages - 1; p >= 0; --p) e->free_pages.push_back((int32_t)p);   // page 0 is handed out first
+  e->st.kv_pages_total = n_pages;
 }
 
 template <typename T>
@@ -195,11 +218,6 @@ int alloc_device(pl_engine *e) {
   int rc;
   for (int b = 0; b < c.n_weight_buffers; ++b)
     if ((rc = dev_alloc(&e->wbuf[b], e->blob_elems))) return rc;
-  const int64_t pool_elems = e->layer_stride * c.n_layers;
-  if ((rc = dev_alloc(&e->kv_pool, pool_elems))) return rc;
-  // Every position a kernel may touch must hold a finite value: masked soft-max weights are
-  // exactly 0, and 0 * finite stays 0.
-  HIP_TRY(hipMemsetAsync(e->kv_pool, 0, (size_t)pool_elems * 2, e->s_dec));
   const int B = c.max_batch;
   const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
   const int64_t wq = qd + 2 * kvd;
@@ -232,6 +250,23 @@ int alloc_device(pl_engine *e) {
   char *ws = nullptr;
   if ((rc = dev_alloc(&ws, pl::sample_workspace_bytes(B, c.vocab)))) return rc;
   e->samp_ws = ws;
+  // the KV pool comes last: with kv_pool_tokens == 0 it takes what is left of the device memory, minus
+  // a reserve for the caller, up to the most the slots could ever use
+  if (e->n_pages == 0) {
+    size_t free_b = 0, total_b = 0;
+    HIP_TRY(hipMemGetInfo(&free_b, &total_b));
+    const int64_t page_bytes = e->page_stride * 2 * std::max(c.n_layers, 1);
+    const int64_t avail = (int64_t)free_b - KV_AUTO_RESERVE_BYTES;
+    const int64_t most = (int64_t)B * e->pages_per_seq;
+    e->n_pages = std::min(avail > 0 ? avail / page_bytes : 0, most);
+    if (e->n_pages < 1) return fail(PL_E_NOMEM, "no device memory left for a KV pool (%lld bytes free)", (long long)free_b);
+    set_pool_pages(e, e->n_pages);
+  }
+  const int64_t pool_elems = e->layer_stride * c.n_layers;
+  if ((rc = dev_alloc(&e->kv_pool, pool_elems))) return rc;
+  // Every position a kernel may touch must hold a finite value: masked soft-max weights are
+  // exactly 0, and 0 * finite stays 0.
+  HIP_TRY(hipMemsetAsync(e->kv_pool, 0, (size_t)pool_elems * 2, e->s_dec));
   HIP_TRY(hipHostMalloc((void **)&e->pt_h, (size_t)B * e->pages_per_seq * 4, hipHostMallocDefault));
   HIP_TRY(hipHostMalloc((void **)&e->meta_h, (size_t)e->meta_bytes, hipHostMallocDefault));
   HIP_TRY(hipHostMalloc((void **)&e->tok_h, (size_t)B * 4, hipHostMallocDefault));
@@ -278,8 +313,8 @@ int enqueue_step(pl_engine *e, int n, bool prefill = false) {
   const bf16_t *lm = base + e->layout.back().offset;
   int rc = 0;
   rc |= pl::launch_rope_tables(e->m_pos(true), e->cs, e->ctx_len, n, c.head_dim, c.rope_theta, s);
-  rc |= pl::launch_attention_worklist(e->ctx_len, e->m_row_slot(true), e->pt_d, e->attn_work, n, e->attn_chunk,
-                                      e->page_tokens, e->pages_per_seq, s);
+  rc |= pl::launch_attention_worklist(e->ctx_len, e->m_row_slot(true), e->pt_d, e->attn_work, n, e->attn_max_chunks,
+                                      e->attn_chunk, e->page_tokens, e->pages_per_seq, s);
   const bf16_t *g_first = c.n_layers ? layer_weights(e, 0).g1 : gf;
   rc |= pl::launch_embed_rmsnorm(embed, g_first, e->m_input(true), nullptr, e->m_row_slot(true), e->h, e->a, n,
                                  d, c.vocab, c.rms_eps, s);
@@ -299,6 +334,7 @@ int enqueue_step(pl_engine *e, int n, bool prefill = false) {
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
     ap.max_chunks = e->attn_max_chunks;
     ap.work = e->attn_work; ap.max_items = e->attn_items;
+    ap.multi = pl::attention_multi_list(e->attn_work, n, e->attn_max_chunks); ap.max_multi = e->attn_multi;
     if (prefill && l + 1 == c.n_layers) break;
     mark(e, CAT_OTHER, true);
     rc |= pl::launch_attention(ap, s);
@@ -393,7 +429,7 @@ int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::ve
   const size_t total = slots.size();
   for (size_t r0 = 0; r0 < total; r0 += rows_max) {
     const int n = (int)std::min<size_t>(rows_max, total - r0);
-    int items = 0;
+    int items = 0, multi = 0;
     for (int r = 0; r < n; ++r) {
       const Seq &q = e->seqs[slots[r0 + r]];
       row_slot[r] = slots[r0 + r];
@@ -403,8 +439,10 @@ int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::ve
       inv_t[r] = q.inv_t;
       sid[r] = q.seq_id;
       items += (pos[r] + 1 + e->attn_chunk - 1) / e->attn_chunk;
+      multi += pos[r] + 1 > e->attn_chunk;
     }
     e->attn_items = items;
+    e->attn_multi = multi;
     if (!e->dry) {
       hipStream_t s = e->s_dec;
       if (e->pt_dirty) {
@@ -467,20 +505,23 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
   e->G = cfg->n_q_heads / cfg->n_kv_heads;
   e->page_tokens = cfg->kv_page_tokens ? cfg->kv_page_tokens : 128;
   e->pages_per_seq = (cfg->max_context + e->page_tokens - 1) / e->page_tokens;
-  e->n_pages = cfg->kv_pool_tokens / e->page_tokens;
-  if (e->n_pages < 1 || e->n_pages > 0x7FFFFFFF) {
+  e->page_stride = (int64_t)cfg->n_kv_heads * 2 * e->page_tokens * cfg->head_dim;
+  int64_t n_pages = cfg->kv_pool_tokens / e->page_tokens;
+  if (cfg->kv_pool_tokens == 0)   // automatic: a bookkeeping-only engine gets the most its slots can use
+    n_pages = e->dry ? (int64_t)cfg->max_batch * e->pages_per_seq : 0;
+  else if (n_pages < 1) {
     delete e;
     return fail(PL_E_INVAL, "kv_pool_tokens must hold at least one page");
   }
-  e->page_stride = (int64_t)cfg->n_kv_heads * 2 * e->page_tokens * cfg->head_dim;
-  e->layer_stride = e->page_stride * e->n_pages;
+  if (n_pages > 0x7FFFFFFF) {
+    delete e;
+    return fail(PL_E_INVAL, "KV pool of more than 2^31 pages");
+  }
   build_layout(e);
   e->seqs.resize(cfg->max_batch);
-  e->free_pages.reserve(e->n_pages);
-  for (int64_t p = e->n_pages - 1; p >= 0; --p) e->free_pages.push_back((int32_t)p);   // page 0 is handed out first
+  set_pool_pages(e, n_pages);
   e->rows_cap = std::max(cfg->max_batch, 256);
   e->meta_bytes = (int64_t)e->rows_cap * (4 * 5 + 8);
-  e->st.kv_pages_total = e->n_pages;
   if (e->dry) {
     e->meta_h = (char *)calloc(1, (size_t)e->meta_bytes);
     if (!e->meta_h) { delete e; return fail(PL_E_NOMEM, "out of host memory"); }
@@ -531,6 +572,53 @@ int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t
 }
 
 int64_t pl_weight_nbytes(const pl_engine *e) { return e ? e->blob_elems * 2 : 0; }
+
+int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32_t src_is_f32, void *blob) {
+  if (!e || !name || !src || !blob) return fail(PL_E_INVAL, "NULL argument");
+  const pl_model_cfg &c = e->cfg;
+  const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
+  // source tensor -> (blob tensor, rows and columns of the source, where its rows go)
+  std::string target = name;
+  int64_t rows = 0, cols = d, row0 = 0;
+  int interleave = -1;   // 0 / 1: gate / up rows of the 32-row interleaved w_gu
+  const size_t dot = target.find('.');
+  const std::string leaf = dot == std::string::npos ? target : target.substr(dot + 1);
+  const std::string pre = dot == std::string::npos ? "" : target.substr(0, dot + 1);
+  if (dot == std::string::npos) {
+    if (leaf == "embed" || leaf == "lm_head") rows = c.vocab;
+    else if (leaf == "gf") { rows = d; cols = 1; }
+    else return fail(PL_E_INVAL, "unknown tensor '%s'", name);
+  } else if (leaf == "g1" || leaf == "g2") { rows = d; cols = 1; }
+  else if (leaf == "wq") { rows = qd; target = pre + "w_qkv"; }
+  else if (leaf == "wk") { rows = kvd; row0 = qd; target = pre + "w_qkv"; }
+  else if (leaf == "wv") { rows = kvd; row0 = qd + kvd; target = pre + "w_qkv"; }
+  else if (leaf == "wo") { rows = d; cols = qd; target = pre + "w_o"; }
+  else if (leaf == "wg") { rows = c.d_ffn; interleave = 0; target = pre + "w_gu"; }
+  else if (leaf == "wu") { rows = c.d_ffn; interleave = 1; target = pre + "w_gu"; }
+  else if (leaf == "wd") { rows = d; cols = c.d_ffn; target = pre + "w_d"; }
+  else return fail(PL_E_INVAL, "unknown tensor '%s'", name);
+  const Tensor *t = nullptr;
+  for (const Tensor &x : e->layout)
+    if (x.name == target) { t = &x; break; }
+  if (!t) return fail(PL_E_INVAL, "unknown tensor '%s'", name);
+  uint16_t *dst = (uint16_t *)blob + t->offset;
+  auto bits = [&](int64_t i) -> uint16_t {
+    return src_is_f32 ? f32_to_bf16_bits(((const float *)src)[i]) : ((const uint16_t *)src)[i];
+  };
+  if (t->cols == 1 || t->name == "embed") {   // stored as they are
+    for (int64_t i = 0; i < rows * cols; ++i) dst[i] = bits(i);
+    return PL_OK;
+  }
+  const int64_t row_blocks = t->rows / 32;
+  for (int64_t r = 0; r < rows; ++r) {
+    const int64_t R = interleave < 0 ? row0 + r : 64 * (r / 32) + 32 * interleave + r % 32;
+    for (int64_t k = 0; k < cols; ++k) {
+      const int64_t o = ((k / 64) * row_blocks + R / 32) * 2048 + ((k % 32) / 8) * 512 + ((k % 64) / 32) * 256 + (R % 32) * 8 + k % 8;
+      dst[o] = bits(r * cols + k);
+    }
+  }
+  return PL_OK;
+}
 
 int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes) {
   if (!e || !src) return fail(PL_E_INVAL, "NULL argument");
@@ -660,6 +748,12 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
 
   // 2. in-flight weight update: flips only here, between two steps
   bool timed_stall = false;
+  if (e->staged && e->staged_recompute)
+    // a slot admitted after the request may lack its history: refuse before anything changes (the
+    // update stays staged; the caller supplies the history or retires the slot and steps again)
+    for (const Seq &q : e->seqs)
+      if (q.active && (!q.hist_known || (int)q.hist.size() < q.pos))
+        return fail(PL_E_STATE, "a slot admitted after the update was requested has no token history; its cache cannot be recomputed");
   if (e->staged) {
     if (e->dry) {
       activate_staged(e);
@@ -673,12 +767,20 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       if (qy == hipSuccess) activate_staged(e);
       else if (qy != hipErrorNotReady) return fail(PL_E_HIP, "hipEventQuery: %s", hipGetErrorString(qy));
     }
+    if (!e->staged && !e->dry && e->poison_inactive && c.n_weight_buffers == 2) {
+      // Nothing may read the old weights after the flip: with every element a bf16 NaN, a kernel that
+      // still does shows up in the logits.  The next staging copy overwrites the buffer; it cannot start
+      // before this step has ended (steps are synchronous), so the fill needs no further ordering.
+      if (pl::launch_fill_u32((uint32_t *)e->wbuf[e->active_buf ^ 1], 0x7FC07FC0u, e->blob_elems / 2, e->s_dec))
+        return fail(PL_E_HIP, "fill launch failed");
+    }
     if (!e->staged && !e->dry) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, e->ev_copy0, e->ev_staged) == hipSuccess) e->st.last_swap_copy_ms = ms;
       (void)hipGetLastError();
     }
     if (!e->staged && e->staged_recompute) {
+
       // the update asked for the caches to be rebuilt under the new weights: do it now, before the
       // first token is produced from them; the time counts as this step's stall
       e->staged_recompute = false;
@@ -697,7 +799,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   uint64_t *sid = e->m_seq_id(false);
   int r = 0;
   double kv_tokens = 0;
-  int items = 0;
+  int items = 0, multi = 0;
   for (int s = 0; s < c.max_batch; ++s) {
     Seq &q = e->seqs[s];
     if (!q.active) continue;
@@ -716,10 +818,12 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     sid[r] = q.seq_id;
     kv_tokens += q.pos;
     items += (q.pos + 1 + e->attn_chunk - 1) / e->attn_chunk;
+    multi += q.pos + 1 > e->attn_chunk;
     ++r;
   }
 
   e->attn_items = items;
+  e->attn_multi = multi;
 
   // 4. run
   if (!e->dry) {
@@ -878,6 +982,12 @@ int pl_debug_set_profile(pl_engine *e, int32_t level) {
   return PL_OK;
 }
 
+int pl_debug_set_poison(pl_engine *e, int32_t on) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  e->poison_inactive = on != 0;
+  return PL_OK;
+}
+
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes) {
   if (!e || !device_ptr || !nbytes) return fail(PL_E_INVAL, "NULL argument");
   if (e->dry) return fail(PL_E_STATE, "bookkeeping-only engine holds no KV");
@@ -915,9 +1025,11 @@ int pl_attention_decode(const void *q, const void *kv_pages, const int32_t *page
   p.part_ml = p.part_o + np * hd;
   int32_t *work = (int32_t *)(((uintptr_t)(p.part_ml + np * 2) + 31) & ~(uintptr_t)31);   // records are read 16 bytes at a time
   p.work = work;
+  p.multi = pl::attention_multi_list(work, n_seq, p.max_chunks);
   p.max_items = n_seq * p.max_chunks;
+  p.max_multi = p.max_chunks > 1 ? n_seq : 0;
   if (n_seq > 1024) return fail(PL_E_INVAL, "at most 1024 sequences per launch");
-  if (pl::launch_attention_worklist(ctx_len, nullptr, page_table, work, n_seq, p.chunk, page_tokens, pages_per_seq, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
+  if (pl::launch_attention_worklist(ctx_len, nullptr, page_table, work, n_seq, p.max_chunks, p.chunk, page_tokens, pages_per_seq, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
   if (pl::launch_attention(p, (hipStream_t)stream)) return fail(PL_E_HIP, "attention launch failed");
   return PL_OK;
 }

@@ -248,3 +248,69 @@ def test_cache_recomputation_bookkeeping():
     with pytest.raises(pl.PlError) as ex:
         e.swap_weights(blob, flags=8)
     assert ex.value.code == pl.PL_E_INVAL
+
+
+def test_c_helper_packs_the_same_blob_as_the_numpy_permutation():
+    """pl_pack_weights (what a C caller uses) against the layout formula of include/pl.h, written out
+    independently in Engine.pack_weights and checked element by element in the layout test above."""
+    e = _engine()
+    W = synth.make_weights(M, 11)
+    assert np.array_equal(e.pack_weights_c(W), e.pack_weights(W, synth.f32_to_bf16_bits))
+    blob = np.zeros(e.weight_nbytes() // 2, np.uint16)
+    bits = synth.f32_to_bf16_bits(W["l1.wd"]).reshape(W["l1.wd"].shape)    # bf16 bit patterns as the source
+    L = pl.lib()
+    assert L.pl_pack_weights(e._h, b"l1.wd", bits.ctypes.data, 0, blob.ctypes.data) == 0
+    d = dict((n, (o, s)) for n, o, s in e.weight_layout())
+    o, (r, c) = d["l1.w_d"]
+    assert np.array_equal(blob[o:o + r * c], pl.operand_order(bits))
+    assert L.pl_pack_weights(e._h, b"l9.wq", bits.ctypes.data, 0, blob.ctypes.data) == pl.PL_E_INVAL
+    assert L.pl_pack_weights(e._h, b"l0.wx", bits.ctypes.data, 0, blob.ctypes.data) == pl.PL_E_INVAL
+
+
+def test_kv_pool_sized_automatically_and_bad_pool_sizes():
+    e = _engine(kv_pool_tokens=0, kv_page_tokens=64)              # bookkeeping engine: the most the slots can use
+    assert e.stats()["kv_pages_total"] == 4 * 2
+    with pytest.raises(pl.PlError) as ex:
+        _engine(kv_pool_tokens=-5)
+    assert ex.value.code == pl.PL_E_INVAL
+    with pytest.raises(pl.PlError) as ex:
+        _engine(kv_pool_tokens=10, kv_page_tokens=64)             # less than one page
+    assert ex.value.code == pl.PL_E_INVAL
+
+
+def test_create_rejects_a_weight_matrix_the_gemm_cannot_address():
+    """vocab x d_model x 2 bytes >= 2 GiB would wrap the GEMM's 32-bit buffer addressing."""
+    big = synth.ModelCfg(1, 8192, 64, 8, 128, 8192, 131072 + 32)
+    with pytest.raises(pl.PlError) as ex:
+        pl.Engine.from_model(big, max_batch=2, max_context=64, kv_pool_tokens=128, device=pl.PL_DEVICE_NONE)
+    assert ex.value.code == pl.PL_E_INVAL and "2 GiB" in str(ex.value)
+    ok = synth.ModelCfg(1, 8192, 64, 8, 128, 8192, 131072 - 32)
+    pl.Engine.from_model(ok, max_batch=2, max_context=64, kv_pool_tokens=128, device=pl.PL_DEVICE_NONE).close()
+
+
+def test_odd_batch_sizes_keep_the_step_metadata_aligned():
+    """Every per-row array of the step metadata must be aligned for its type at any max_batch."""
+    for B in (1, 3, 257, 511):
+        e = _loaded(max_batch=B, kv_pool_tokens=64 * B)
+        ids = [(1 << 40) + 7 * i for i in range(B)]
+        for i in range(B):
+            e.add_sequence(ids[i], [1, 2], 2)
+        r = e.decode_step()
+        assert r["n"] == B and r["seq_id"].tolist() == ids
+        e.close()
+
+
+def test_recomputation_is_refused_at_the_flip_if_a_slot_lost_its_history_meanwhile():
+    e = _loaded()
+    e.add_sequence(1, [5, 6, 7], 10)
+    e.decode_step()
+    blob = np.zeros(e.weight_nbytes() // 2, np.uint16)
+    e.swap_weights(blob, flags=pl.PL_SWAP_ASYNC | pl.PL_SWAP_RECOMPUTE_KV)
+    s1 = e.debug_add_sequence_at(9, None, 16, 64, 1.0, context_len=20, n_emitted=5, last_token=3)   # after the request
+    with pytest.raises(pl.PlError) as ex:
+        e.decode_step()
+    assert ex.value.code == pl.PL_E_STATE
+    assert e.swap_poll() == (True, 0) and e.stats()["steps"] == 1    # nothing changed: still staged, old version
+    e.debug_set_history(s1, np.arange(20))
+    r = e.decode_step()
+    assert r["weight_version"].tolist() == [1, 1] and e.stats()["recompute_positions"] == 1 + 20

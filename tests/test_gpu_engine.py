@@ -217,8 +217,113 @@ def test_post_swap_steps_follow_new_weights_over_the_retained_cache(weights):
     eng.close()
 
 
+def _forced_run(eng, orc, forced_stream, batch, steps, check_version=None):
+    """Engine first, then the oracle under the weight version the engine's step reported: both consume
+    the same pre-drawn forced tokens, so the order of the two calls does not matter."""
+    for _ in range(steps):
+        f = next(forced_stream)
+        out = eng.decode_step(f)
+        ver = int(out["weight_version"][0])
+        assert (out["weight_version"] == ver).all()
+        if check_version is not None:
+            assert ver == check_version
+        yield ver, out, f
+
+
+def test_in_flight_update_staged_in_the_background_flips_between_two_steps(weights):
+    """PL_SWAP_ASYNC, the mode the benchmark runs: the blob is copied on the side stream while steps go
+    on; every step must compute wholly under the version it reports (old before the flip, new from the
+    flip on, never a mixture), and once the copy is reported complete the very next step must flip.
+    Alg. 2's update branch with Sec. 5.1's retained cache, checked on the device against the oracle."""
+    import torch
+    master, pert = weights
+    batch = 4
+    eng = _engine(batch)
+    blobs = [eng.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
+    eng.load_weights(blobs[0])
+    pinned = torch.from_numpy(blobs[1].view(np.int16)).pin_memory()
+    orc = OracleEngine(M, _rounded(master), max_batch=batch, seed=SEED)
+    rng = np.random.default_rng(99)
+    prompts = synth.random_prompts(rng, batch, 6, M.vocab)
+    for i in range(batch):
+        eng.add_sequence(50 + i, prompts[i], 60); orc.add_sequence(50 + i, prompts[i], 60)
+
+    def stream():
+        while True:
+            yield rng.integers(0, M.vocab, batch).astype(np.int32)
+
+    def compare(out, f):
+        recs = orc.decode_step(f)
+        lg = eng.debug_get_logits(out["n"])
+        for i, r in enumerate(recs):
+            assert out["weight_version"][i] == r.weight_version
+            assert out["token"][i] == r.token
+            ok, err = close(lg[i], orc.last_logits[r.slot], ATOL, RTOL)
+            assert ok, (r.position, err)
+            assert abs(out["logprob"][i] - r.logprob) <= ATOL + RTOL * abs(r.logprob)
+
+    fs = stream()
+    for ver, out, f in _forced_run(eng, orc, fs, batch, 8, check_version=0):
+        compare(out, f)
+    assert eng.swap_weights(pinned.data_ptr(), eng.weight_nbytes(), flags=pl.PL_SWAP_ASYNC) == 1
+    seen = []
+    for _ in range(200):                               # steps while the copy may still be in flight
+        ready, active = eng.swap_poll()
+        ver, out, f = next(_forced_run(eng, orc, fs, batch, 1))
+        if ver == 1 and orc.version == 0:
+            orc.swap_weights(_rounded(pert))           # the flip happened at this step's boundary
+        compare(out, f)
+        seen.append(ver)
+        if ready:
+            assert ver == 1, "the copy was complete before the step, so the step must have flipped"
+        if ver == 1:
+            break
+    assert seen[-1] == 1 and seen == sorted(seen) and len(seen) < 40
+    assert eng.swap_poll() == (False, 1)
+    for ver, out, f in _forced_run(eng, orc, fs, batch, 6, check_version=1):
+        compare(out, f)
+    eng.close()
+
+
+def test_buffer_that_went_inactive_can_be_poisoned_and_nothing_reads_it(weights):
+    """Debugging aid: with pl_debug_set_poison the buffer that just went inactive is filled with NaN at
+    the flip.  A full update cycle (two flips, so each buffer is poisoned once and reloaded once) must
+    stay finite and must equal, bit for bit, the same run without the poison."""
+    master, pert = weights
+    runs = []
+    for poison in (False, True):
+        eng = _engine()
+        blobs = [eng.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
+        eng.load_weights(blobs[0])
+        eng.debug_set_poison(poison)
+        prompts = synth.random_prompts(np.random.default_rng(8), 4, 5, M.vocab)
+        for i in range(4):
+            eng.add_sequence(i, prompts[i], 40)
+        lgs = []
+        for s in range(30):
+            if s in (6, 14, 22):
+                eng.swap_weights(blobs[(s // 8 + 1) % 2], flags=pl.PL_SWAP_WAIT)
+            o = eng.decode_step()
+            lg = eng.debug_get_logits(o["n"])
+            assert np.isfinite(lg).all() and np.isfinite(o["logprob"]).all(), s
+            lgs.append((o["token"].copy(), o["weight_version"].copy(), lg))
+        assert eng.stats()["swaps"] == 3
+        runs.append(lgs)
+        eng.close()
+    for a, b in zip(*runs):
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+def test_kv_pool_sized_from_free_device_memory():
+    """kv_pool_tokens = 0: the pool takes what is free, capped at what the slots can ever use."""
+    eng = _engine(kv_pool_tokens=0, max_context=128, kv_page_tokens=32)
+    st = eng.stats()
+    assert st["kv_pages_total"] == 4 * 4 and st["kv_pages_free"] == 16
+    eng.close()
+
+
 @pytest.mark.parametrize("name,batch,ctx", [("1p5b", 2, 48), ("7b", 2, 40), ("32b", 2, 20)])
-def test_one_layer_slice_of_the_large_shapes(name, batch, ctx):
+def test_one_layer_slice_of_the_large_shapes_error_rms_below_one_percent_of_the_logit_rms(name, batch, ctx):
     """One layer + LM head at the 1.5B / 7B / 32B shapes (real head counts, widths and vocabulary), a couple
     of rows, short contexts: the oracle runs in float32 here to bound its memory."""
     m = synth.CONFIGS[name].with_layers(1)

@@ -128,11 +128,11 @@ def test_bench_configuration_sampled_rows_against_oracle(full):
         err = logits[r] - ref
         rel = float(err.std() / ref.std())
         print(f"row {r}: context {int(pos1[r]) + 1}, logit rms {ref.std():.3f}, error rms {err.std():.4f} ({100 * rel:.2f} %), max {np.abs(err).max():.4f}")
-        # 28 layers of bf16 rounding stages (see the one-layer slice test): the per-layer noise of about
-        # 0.6 % of the logit scale adds in quadrature over depth
-        assert rel <= 0.006 * np.sqrt(m.n_layers) * 1.5, (r, rel)
-        scale = max(1.0, float(ref.std()) / 0.32) * np.sqrt(m.n_layers)
-        assert close(logits[r], ref, 2e-2 * scale, 1e-2)[0], r
+        # 28 layers of bf16 rounding stages: the binding check is the error rms against the logit rms
+        # (measured 2.0-2.8 % in these configurations; test_error_grows_like_the_root_of_the_depth shows
+        # where that figure comes from layer by layer).  An element-wise bound scaled to this depth would
+        # be too wide to fail and is not asserted; a wrong index or head mapping gives errors of order 100 %.
+        assert rel <= 0.036, (r, rel)
         assert int(np.argmax(logits[r])) in np.argsort(ref)[-5:]
 
 
@@ -176,3 +176,42 @@ def test_batched_prompt_reading_at_full_size(full):
         assert ok, ("K", p, err)
         ok, err = close(kv_a[0][1][p], v, 2e-2 * scale, 1e-2)
         assert ok, ("V", p, err)
+
+
+def test_error_grows_like_the_root_of_the_depth():
+    """bf16 rounding noise against the fp32 oracle as a function of depth, at the 1.5B widths (real head
+    counts, FFN width and vocabulary): engines of 1, 2, 4, 8, 16 and 28 layers built from the first layers of
+    one 28-layer weight set, the same prompt, logits of the last positions.  Each layer adds independent
+    noise of about the same size, so the error rms may grow at most like sqrt(depth) from the one-layer
+    figure (it grows more slowly in fact, because the residual stream grows too); a mistake confined to
+    some layer index or to deep stacks shows up as a jump between two depths."""
+    full = synth.CONFIGS["1p5b"]
+    depths = [1, 2, 4, 8, 16, 28]
+    w_all = synth.make_weights(full, seed=777)
+    prompt = synth.random_prompts(np.random.default_rng(778), 1, 10, full.vocab)[0]
+    rel = {}
+    for L in depths:
+        m = full.with_layers(L)
+        names = set(synth.weight_names(m))
+        w = {k: v for k, v in w_all.items() if k in names}
+        eng = pl.Engine.from_model(m, max_batch=1, max_context=64, kv_pool_tokens=128, seed=3, device=0)
+        eng.load_weights(eng.pack_weights(w, synth.f32_to_bf16_bits))
+        wr = {k: synth.bf16_round(v) for k, v in w.items()}
+        eng.add_sequence(1, prompt, 4)
+        cache = decoder.Cache(m, np.float32)
+        errs, refs = [], []
+        for p, tok in enumerate(prompt):
+            out = eng.decode_step(np.array([int(prompt[p + 1]) if p + 1 < len(prompt) else 0], np.int32))
+            ref = decoder.step(m, wr, int(tok), p, cache, np.float32)
+            if p >= len(prompt) - 3:
+                lg = eng.debug_get_logits(1)[0]
+                errs.append(lg - ref); refs.append(ref)
+        eng.close()
+        rel[L] = float(np.concatenate(errs).std() / np.concatenate(refs).std())
+        print(f"depth {L:2d}: error rms {100 * rel[L]:.2f} % of the logit rms", flush=True)
+    assert rel[1] <= 0.01
+    for a, b in zip(depths, depths[1:]):
+        assert rel[b] <= 1.3 * np.sqrt(b / a) * rel[a], (a, b, rel)          # no jump between two depths
+        assert rel[b] >= 0.7 * rel[a], (a, b, rel)                            # noise does not vanish with depth
+    for L in depths:
+        assert rel[L] <= 1.3 * np.sqrt(L) * rel[1], (L, rel)
