@@ -580,15 +580,37 @@ def main():
 
     # Updates arrive every `swap_every` steps; where that cycle stands when the timed window opens is
     # arbitrary.  A window of at least one period takes the first request half a period in.  A shorter
-    # window would otherwise contain no update at all, so its request is issued when the warm-up starts:
-    # the staging copy is then in flight over the first timed steps and the flip falls inside the window
-    # (this charges the window one update per `steps` instead of one per `swap_every`).
+    # window would otherwise contain no update at all, so its one request is issued during the warm-up, at
+    # the step from which the staging copy (its duration predicted from a timed 256 MiB copy out of the same
+    # pinned buffer) ends nearest the middle of the timed window: the window then holds steps that overlap
+    # the copy, the flip, and steps after it (this charges the window one update per `steps` instead of
+    # one per `swap_every`).  If the copy outlasts warm-up + window, the line says the window holds no flip.
     every = spec["swap_every"]
     short_window = bool(every) and args.steps < every
+    copy_est = None
     if short_window:
-        request_update(-args.warmup)
-    for _ in range(args.warmup):
+        n_probe = min(host[0].numel(), 1 << 27)
+        probe = torch.empty(n_probe, dtype=torch.bfloat16, device="cuda")
+        probe.copy_(host[0][:n_probe], non_blocking=True)
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        probe.copy_(host[0][:n_probe], non_blocking=True)
+        torch.cuda.synchronize()
+        copy_est = (time.perf_counter() - tp) * host[0].numel() / n_probe
+        del probe
+    warm_wall = []
+    for i in range(args.warmup):
+        if short_window and not requests and i >= min(2, args.warmup - 1):
+            # wall time of a step from the warm-up steps so far (the first one pays one-off start-up costs)
+            est = float(np.mean(warm_wall[1:])) if len(warm_wall) > 1 else None
+            lands = None if est is None else (copy_est - (args.warmup - i) * est) / (args.steps * est)
+            if lands is None or lands >= 0.3 or i == args.warmup - 1:
+                request_update(i - args.warmup)
+        tw = time.perf_counter()
         wl.step()
+        warm_wall.append(time.perf_counter() - tw)
+    if short_window and not requests:
+        request_update(0)
     torch.cuda.synchronize()
     s0 = eng.stats()
     emitted = 0
