@@ -170,7 +170,9 @@ class Workload:
             prompt = synth.random_prompts(self.rng, 1, P, self.model.vocab)[0]
             slot = self.eng.add_sequence(self.next_id, prompt, self._new_len(), 1.0)
             self.order.append(slot)
-            if self.batched_prefill:
+            if self.batched_prefill == "background":
+                self.eng.prefill_async(slot)
+            elif self.batched_prefill:
                 self.eng.prefill(slot)
             self.next_id += 1
 
@@ -513,8 +515,9 @@ def main():
     ap.add_argument("--steps", type=int, default=1024)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="7b", choices=sorted(WORKLOADS))
-    ap.add_argument("--prefill", default="batched", choices=["batched", "decode"],
-                    help="how a refilled slot reads its prompt: batched passes at admission, or one token per decode step")
+    ap.add_argument("--prefill", default="background", choices=["background", "batched", "decode"],
+                    help="how a refilled slot reads its prompt: batched passes on a stream of their own while the other "
+                         "slots keep decoding, batched passes that block, or one token per decode step")
     ap.add_argument("--recompute-kv", action="store_true",
                     help="weight updates rebuild every sequence's KV cache under the new weights (Sec. 5.1 variant; slow)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -560,7 +563,8 @@ def main():
         torch.cuda.empty_cache()
     fill_kv_pool(eng, torch, seed=1239)
 
-    wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill=args.prefill == "batched", keep_history=args.recompute_kv)
+    wl = Workload(eng, spec, model, seed=1234 + 3, batched_prefill={"background": "background", "batched": True, "decode": False}[args.prefill],
+                  keep_history=args.recompute_kv)
     wl.admit_steady_state()
     eng.debug_set_profile(0 if args.no_profile else 1)   # events around the attention launches only
     step_ms, stalls, flips, requests = [], [], [], []
@@ -611,7 +615,8 @@ def main():
         warm_wall.append(time.perf_counter() - tw)
     if short_window and not requests:
         request_update(0)
-    torch.cuda.synchronize()
+    # no device-wide synchronisation here: it would wait for the staging copy; every step has already
+    # returned its tokens, so the decode stream is idle
     s0 = eng.stats()
     emitted = 0
     last_version = s0["active_version"]
@@ -666,7 +671,8 @@ def main():
         "config": {"workload": f"{args.workload}-shaped decoder, constant batch {spec['batch']} with continuous refill, "
                                f"{spec['prompt']}-token prompts, lognormal(mean {spec['mean']:.0f}, sigma 0.75, max {spec['gmax']}) "
                                f"generation lengths, steady-state ages, weight update from pinned host every {spec['swap_every']} steps, "
-                               f"prompts read {'in batched passes at admission' if args.prefill == 'batched' else 'one token per step'}",
+                               "prompts read " + {"background": "in batched passes in the background, overlapped with decode steps",
+                                                   "batched": "in batched passes at admission", "decode": "one token per step"}[args.prefill],
                    "mean_context": d["algorithmic_bytes"] and float((d["attn_kv_bytes"] / max(d["attn_launches"], 1)) /
                                                                     (4.0 * model.n_kv_heads * model.head_dim) / spec["batch"]),
                    "slot_utilisation": d["tokens_emitted"] / max(d["slot_steps"], 1),

@@ -187,6 +187,17 @@ int pl_add_sequence(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_
  * *out_positions (may be NULL) receives the number of positions read (0 if none were left).
  * Blocks until done.  PL_E_STATE if the slot is idle or before pl_load_weights. */
 int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions);
+/* The same reading, in the background: the passes are enqueued on a stream of their own and the call
+ * returns at once, so decode steps of the other slots go on meanwhile (the passes are GEMM-bound, the
+ * decode step mostly waits for K/V bytes; the two overlap on the GPU).  Until its passes have finished
+ * the slot takes no part in decode steps: pl_decode_step leaves it out (its entry is simply missing
+ * from that step's output) and includes it from the first step that finds the reading complete; a
+ * step with no other occupied slot waits for it.  What a sequence produces does not depend on when it
+ * joins: its cache, logits and draws are those of pl_prefill.  The prompt is read under the weights
+ * active at this call even if an update becomes active meanwhile (the next staging copy waits for the
+ * passes that still read the old buffer).  pl_retire_sequence on such a slot waits for its passes;
+ * an update with PL_SWAP_RECOMPUTE_KV waits for all of them.  PL_E_BUSY if the slot is already reading. */
+int pl_prefill_async(pl_engine *e, int32_t slot, int32_t *out_positions);
 /* Free a slot and its KV pages (finished or not).  PL_E_STATE if the slot is idle. */
 int pl_retire_sequence(pl_engine *e, int32_t slot);
 int32_t pl_num_active(const pl_engine *e);

@@ -20,7 +20,7 @@ PL_DEVICE_NONE = -1
 # every symbol include/pl.h declares
 EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
-    "pl_pack_weights", "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_retire_sequence",
+    "pl_pack_weights", "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_prefill_async", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
     "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample", "pl_is_ess",
@@ -92,6 +92,7 @@ def lib():
         "pl_swap_poll": (C.c_int, [vp, P(i32), P(u32)]),
         "pl_add_sequence": (C.c_int, [vp, u64, vp, i32, i32, f32, P(i32)]),
         "pl_prefill": (C.c_int, [vp, i32, P(i32)]),
+        "pl_prefill_async": (C.c_int, [vp, i32, P(i32)]),
         "pl_debug_set_history": (C.c_int, [vp, i32, vp, i32]),
         "pl_retire_sequence": (C.c_int, [vp, i32]),
         "pl_num_active": (i32, [vp]),
@@ -286,6 +287,12 @@ class Engine:
         """Read the slot's prompt except its last token in batched passes; returns the positions read."""
         n = C.c_int32()
         _check(lib().pl_prefill(self._h, slot, C.byref(n)))
+        return n.value
+
+    def prefill_async(self, slot):
+        """Start reading the slot's prompt in the background; returns the positions that will be read."""
+        n = C.c_int32()
+        _check(lib().pl_prefill_async(self._h, slot, C.byref(n)))
         return n.value
 
     def debug_set_history(self, slot, tokens):

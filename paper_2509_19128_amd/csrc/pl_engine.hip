@@ -58,6 +58,7 @@ struct Seq {
   std::vector<int32_t> prompt;
   std::vector<int32_t> hist;   // tokens read at positions [0, pos) (what a cache recomputation replays)
   bool hist_known = true;      // false for sequences admitted mid-life without their history
+  bool reading = false;        // its prompt is being read in the background; not part of decode steps yet
   int32_t n_prompt = 0, max_new = 0, pos = 0, n_emitted = 0, next_input = -1;
   float inv_t = 1.f;
   std::vector<int32_t> pages;
@@ -91,15 +92,44 @@ struct pl_engine {
   int32_t *pt_h = nullptr, *pt_d = nullptr;
   bool pt_dirty = false;
   std::vector<Seq> seqs;
-  // per-step metadata: host (pinned) and device images, same layout
-  char *meta_h = nullptr, *meta_d = nullptr;
+  // Activation buffers and per-pass metadata come in two sets, each with its own stream: set 0 is the
+  // decode step's, set 1 belongs to the cache-only passes (prompt reading, cache recomputation), so
+  // that a prompt can be read in the background while decode steps go on.
+  struct Work {
+    hipStream_t stream = nullptr;
+    int rows_cap = 0;
+    char *meta_h = nullptr, *meta_d = nullptr;   // per-pass metadata: host (pinned) and device images, same layout
+    float *h = nullptr, *parts = nullptr, *cs = nullptr, *attn_po = nullptr, *attn_pml = nullptr;
+    bf16_t *a = nullptr, *q_rot = nullptr, *attn_out = nullptr, *mid = nullptr;
+    int32_t *ctx_len = nullptr, *attn_work = nullptr;
+    int attn_items = 0;   // bound on this pass's attention work items
+    int attn_multi = 0;   // rows of this pass that span more than one attention chunk
+    // the 8-byte ids come first, so every array is aligned for its type whatever rows_cap is
+    uint64_t *m_seq_id(bool dev) { return (uint64_t *)(dev ? meta_d : meta_h); }
+    int32_t *m_row_slot(bool dev) { return (int32_t *)(m_seq_id(dev) + rows_cap); }
+    int32_t *m_pos(bool dev) { return m_row_slot(dev) + rows_cap; }
+    int32_t *m_input(bool dev) { return m_pos(dev) + rows_cap; }
+    int32_t *m_forced(bool dev) { return m_input(dev) + rows_cap; }
+    float *m_inv_t(bool dev) { return (float *)(m_forced(dev) + rows_cap); }
+  };
+  Work wk[2];
   int64_t meta_bytes = 0;
-  // work buffers
-  float *h = nullptr, *parts = nullptr, *logits = nullptr, *cs = nullptr, *attn_po = nullptr, *attn_pml = nullptr;
-  bf16_t *a = nullptr, *q_rot = nullptr, *attn_out = nullptr, *mid = nullptr;
-  int32_t *ctx_len = nullptr, *tok_d = nullptr, *attn_work = nullptr;
-  int attn_items = 0;   // bound on this step's attention work items
-  int attn_multi = 0;   // rows of this step that span more than one attention chunk
+  // Host images of the cache-only passes in flight: a pass's image must stay intact until its copy to
+  // the device has run, so the passes take images from a ring; each entry carries the events that
+  // time its pass.
+  struct PassImage {
+    char *meta_h = nullptr;
+    hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+    bool pending = false;
+    double *ms_into = nullptr;
+  };
+  std::vector<PassImage> ring;
+  size_t ring_next = 0;
+  std::vector<hipEvent_t> ev_slot;   // per slot: end of its background prompt reading
+  hipEvent_t ev_pre_last = nullptr;  // end of the last cache-only pass enqueued
+  bool pre_pending = false;          // a cache-only pass may still be running
+  float *logits = nullptr;
+  int32_t *tok_d = nullptr;
   float *lp_d = nullptr;
   void *samp_ws = nullptr;
   int32_t *tok_h = nullptr;
@@ -119,14 +149,6 @@ struct pl_engine {
   int last_n = 0;
   pl_stats st{};
   int64_t streamed_weight_bytes = 0;
-
-  // the 8-byte ids come first, so every array is aligned for its type whatever rows_cap is
-  uint64_t *m_seq_id(bool dev) { return (uint64_t *)(dev ? meta_d : meta_h); }
-  int32_t *m_row_slot(bool dev) { return (int32_t *)(m_seq_id(dev) + rows_cap); }
-  int32_t *m_pos(bool dev) { return m_row_slot(dev) + rows_cap; }
-  int32_t *m_input(bool dev) { return m_pos(dev) + rows_cap; }
-  int32_t *m_forced(bool dev) { return m_input(dev) + rows_cap; }
-  float *m_inv_t(bool dev) { return (float *)(m_forced(dev) + rows_cap); }
 
   const bf16_t *wptr(int buf, const char *name) const {
     for (auto &t : layout)
@@ -205,16 +227,50 @@ int dev_alloc(T **p, int64_t n_elems) {
   return PL_OK;
 }
 
+int alloc_work(pl_engine *e, pl_engine::Work &w, int64_t R, int64_t parts_elems, bool pinned_image) {
+  const pl_model_cfg &c = e->cfg;
+  const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim;
+  int rc;
+  w.rows_cap = (int)R;
+  if ((rc = dev_alloc(&w.meta_d, e->meta_bytes))) return rc;
+  if ((rc = dev_alloc(&w.h, R * d))) return rc;
+  if ((rc = dev_alloc(&w.a, R * d))) return rc;
+  if ((rc = dev_alloc(&w.parts, parts_elems))) return rc;
+  if ((rc = dev_alloc(&w.q_rot, R * qd))) return rc;
+  if ((rc = dev_alloc(&w.attn_out, R * qd))) return rc;
+  if ((rc = dev_alloc(&w.mid, R * c.d_ffn))) return rc;
+  if ((rc = dev_alloc(&w.cs, R * c.head_dim))) return rc;
+  if ((rc = dev_alloc(&w.ctx_len, R))) return rc;
+  const int64_t np = R * c.n_kv_heads * e->attn_max_chunks * e->G;
+  if ((rc = dev_alloc(&w.attn_po, np * c.head_dim))) return rc;
+  if ((rc = dev_alloc(&w.attn_pml, np * 2))) return rc;
+  if ((rc = dev_alloc(&w.attn_work, pl::attention_worklist_ints((int)R, e->attn_max_chunks)))) return rc;
+  if (pinned_image) HIP_TRY(hipHostMalloc((void **)&w.meta_h, (size_t)e->meta_bytes, hipHostMallocDefault));
+  return PL_OK;
+}
+
+void free_work(pl_engine::Work &w) {
+  void *dev[] = {w.meta_d, w.h, w.a, w.parts, w.q_rot, w.attn_out, w.mid, w.cs, w.ctx_len, w.attn_po, w.attn_pml, w.attn_work};
+  for (void *p : dev)
+    if (p) (void)hipFree(p);
+  w = pl_engine::Work{};
+}
+
+constexpr int PASS_RING = 8;   // host metadata images of cache-only passes that may wait on the device at once
+
 int alloc_device(pl_engine *e) {
   const pl_model_cfg &c = e->cfg;
   HIP_TRY(hipSetDevice(c.device));
   HIP_TRY(hipStreamCreateWithFlags(&e->s_dec, hipStreamNonBlocking));
   HIP_TRY(hipStreamCreateWithFlags(&e->s_copy, hipStreamNonBlocking));
+  HIP_TRY(hipStreamCreateWithFlags(&e->wk[1].stream, hipStreamNonBlocking));
+  e->wk[0].stream = e->s_dec;
   HIP_TRY(hipEventCreate(&e->ev_a));
   HIP_TRY(hipEventCreate(&e->ev_b));
   HIP_TRY(hipEventCreate(&e->ev_c));
   HIP_TRY(hipEventCreate(&e->ev_staged));
   HIP_TRY(hipEventCreate(&e->ev_copy0));
+  HIP_TRY(hipEventCreateWithFlags(&e->ev_pre_last, hipEventDisableTiming));
   int rc;
   for (int b = 0; b < c.n_weight_buffers; ++b)
     if ((rc = dev_alloc(&e->wbuf[b], e->blob_elems))) return rc;
@@ -225,28 +281,25 @@ int alloc_device(pl_engine *e) {
   e->sp_o = pl::gemm_pick_splits(B, (int)d, (int)qd);
   e->sp_d = pl::gemm_pick_splits(B, (int)d, c.d_ffn);
   const int64_t R = e->rows_cap;   // rows of the activation buffers (cache-only passes take up to 256 rows)
-  int64_t parts = std::max(std::max(e->sp_qkv * wq, e->sp_o * d), e->sp_d * d) * R;
-  if ((rc = dev_alloc(&e->pt_d, (int64_t)B * e->pages_per_seq))) return rc;
-  if ((rc = dev_alloc(&e->meta_d, e->meta_bytes))) return rc;
-  if ((rc = dev_alloc(&e->h, R * d))) return rc;
-  if ((rc = dev_alloc(&e->a, R * d))) return rc;
-  if ((rc = dev_alloc(&e->parts, parts))) return rc;
-  if ((rc = dev_alloc(&e->q_rot, R * qd))) return rc;
-  if ((rc = dev_alloc(&e->attn_out, R * qd))) return rc;
-  if ((rc = dev_alloc(&e->mid, R * c.d_ffn))) return rc;
-  if ((rc = dev_alloc(&e->logits, (int64_t)B * c.vocab))) return rc;
-  if ((rc = dev_alloc(&e->cs, R * c.head_dim))) return rc;
-  if ((rc = dev_alloc(&e->ctx_len, R))) return rc;
-  if ((rc = dev_alloc(&e->tok_d, B))) return rc;
-  if ((rc = dev_alloc(&e->lp_d, B))) return rc;
+  const int64_t parts = std::max(std::max(e->sp_qkv * wq, e->sp_o * d), e->sp_d * d) * R;
   // the chunk length is fixed by max_batch alone, so a sequence's attention result never depends on
   // how many rows a pass holds
   e->attn_chunk = pl::attention_chunk_tokens(B, c.n_kv_heads, c.max_context);
   e->attn_max_chunks = (c.max_context + e->attn_chunk - 1) / e->attn_chunk;
-  const int64_t np = R * c.n_kv_heads * e->attn_max_chunks * e->G;
-  if ((rc = dev_alloc(&e->attn_po, np * c.head_dim))) return rc;
-  if ((rc = dev_alloc(&e->attn_pml, np * 2))) return rc;
-  if ((rc = dev_alloc(&e->attn_work, pl::attention_worklist_ints((int)R, e->attn_max_chunks)))) return rc;
+  if ((rc = dev_alloc(&e->pt_d, (int64_t)B * e->pages_per_seq))) return rc;
+  if ((rc = alloc_work(e, e->wk[0], R, parts, true))) return rc;
+  if ((rc = alloc_work(e, e->wk[1], R, parts, false))) return rc;
+  e->ring.resize(PASS_RING);
+  for (auto &im : e->ring) {
+    HIP_TRY(hipHostMalloc((void **)&im.meta_h, (size_t)e->meta_bytes, hipHostMallocDefault));
+    HIP_TRY(hipEventCreate(&im.ev_begin));
+    HIP_TRY(hipEventCreate(&im.ev_end));
+  }
+  e->ev_slot.resize(B);
+  for (auto &ev : e->ev_slot) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+  if ((rc = dev_alloc(&e->logits, (int64_t)B * c.vocab))) return rc;
+  if ((rc = dev_alloc(&e->tok_d, B))) return rc;
+  if ((rc = dev_alloc(&e->lp_d, B))) return rc;
   char *ws = nullptr;
   if ((rc = dev_alloc(&ws, pl::sample_workspace_bytes(B, c.vocab)))) return rc;
   e->samp_ws = ws;
@@ -268,7 +321,6 @@ int alloc_device(pl_engine *e) {
   // exactly 0, and 0 * finite stays 0.
   HIP_TRY(hipMemsetAsync(e->kv_pool, 0, (size_t)pool_elems * 2, e->s_dec));
   HIP_TRY(hipHostMalloc((void **)&e->pt_h, (size_t)B * e->pages_per_seq * 4, hipHostMallocDefault));
-  HIP_TRY(hipHostMalloc((void **)&e->meta_h, (size_t)e->meta_bytes, hipHostMallocDefault));
   HIP_TRY(hipHostMalloc((void **)&e->tok_h, (size_t)B * 4, hipHostMallocDefault));
   HIP_TRY(hipHostMalloc((void **)&e->lp_h, (size_t)B * 4, hipHostMallocDefault));
   memset(e->pt_h, 0, (size_t)B * e->pages_per_seq * 4);
@@ -299,63 +351,63 @@ void mark(pl_engine *e, int cat, bool attention_edge = false) {
   (void)hipEventRecord(e->prof_ev[e->prof_n++], e->s_dec);
 }
 
-// prefill: rows are consecutive prompt positions of one slot; only the keys and values they leave in the
-// cache are wanted, so the last layer stops after its append and there is no LM head or sampler.
-int enqueue_step(pl_engine *e, int n, bool prefill = false) {
+// prefill: cache-only pass; only the keys and values the rows leave in the cache are wanted, so the
+// last layer stops after its append and there is no LM head or sampler.  Runs on the work set's stream.
+int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) {
   const pl_model_cfg &c = e->cfg;
-  hipStream_t s = e->s_dec;
-  e->prof_n = 0;
-  mark(e, CAT_OTHER);
+  hipStream_t s = w.stream;
+  const bool timed = !prefill;   // the per-group timers describe decode steps only
+  if (timed) { e->prof_n = 0; mark(e, CAT_OTHER); }
   const bf16_t *base = e->wbuf[e->active_buf];
   const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, wq = qd + 2 * kvd;
   const bf16_t *embed = base + e->layout.front().offset;
   const bf16_t *gf = base + e->layout[e->layout.size() - 2].offset;
   const bf16_t *lm = base + e->layout.back().offset;
   int rc = 0;
-  rc |= pl::launch_rope_tables(e->m_pos(true), e->cs, e->ctx_len, n, c.head_dim, c.rope_theta, s);
-  rc |= pl::launch_attention_worklist(e->ctx_len, e->m_row_slot(true), e->pt_d, e->attn_work, n, e->attn_max_chunks,
+  rc |= pl::launch_rope_tables(w.m_pos(true), w.cs, w.ctx_len, n, c.head_dim, c.rope_theta, s);
+  rc |= pl::launch_attention_worklist(w.ctx_len, w.m_row_slot(true), e->pt_d, w.attn_work, n, e->attn_max_chunks,
                                       e->attn_chunk, e->page_tokens, e->pages_per_seq, s);
   const bf16_t *g_first = c.n_layers ? layer_weights(e, 0).g1 : gf;
-  rc |= pl::launch_embed_rmsnorm(embed, g_first, e->m_input(true), nullptr, e->m_row_slot(true), e->h, e->a, n,
+  rc |= pl::launch_embed_rmsnorm(embed, g_first, w.m_input(true), nullptr, w.m_row_slot(true), w.h, w.a, n,
                                  d, c.vocab, c.rms_eps, s);
   for (int l = 0; l < c.n_layers && !rc; ++l) {
-    const LayerW w = layer_weights(e, l);
+    const LayerW lw = layer_weights(e, l);
     bf16_t *kv_layer = e->kv_pool + (int64_t)l * e->layer_stride;
-    mark(e, CAT_OTHER);
-    rc |= pl::launch_gemm(e->a, w.w_qkv, e->parts, n, wq, d, 0, e->sp_qkv, s);
-    mark(e, CAT_GEMM);
-    rc |= pl::launch_rope_append(e->parts, e->sp_qkv, e->cs, e->m_pos(true), e->m_row_slot(true), e->pt_d,
-                                 e->q_rot, kv_layer, n, c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens,
+    if (timed) mark(e, CAT_OTHER);
+    rc |= pl::launch_gemm(w.a, lw.w_qkv, w.parts, n, wq, d, 0, e->sp_qkv, s);
+    if (timed) mark(e, CAT_GEMM);
+    rc |= pl::launch_rope_append(w.parts, e->sp_qkv, w.cs, w.m_pos(true), w.m_row_slot(true), e->pt_d,
+                                 w.q_rot, kv_layer, n, c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens,
                                  e->pages_per_seq, s);
     pl::AttnParams ap{};
-    ap.q = e->q_rot; ap.kv = kv_layer; ap.page_table = e->pt_d; ap.ctx_len = e->ctx_len;
-    ap.row_slot = e->m_row_slot(true); ap.out = e->attn_out; ap.part_o = e->attn_po; ap.part_ml = e->attn_pml;
+    ap.q = w.q_rot; ap.kv = kv_layer; ap.page_table = e->pt_d; ap.ctx_len = w.ctx_len;
+    ap.row_slot = w.m_row_slot(true); ap.out = w.attn_out; ap.part_o = w.attn_po; ap.part_ml = w.attn_pml;
     ap.n_seq = n; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.hd = c.head_dim;
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
     ap.max_chunks = e->attn_max_chunks;
-    ap.work = e->attn_work; ap.max_items = e->attn_items;
-    ap.multi = pl::attention_multi_list(e->attn_work, n, e->attn_max_chunks); ap.max_multi = e->attn_multi;
+    ap.work = w.attn_work; ap.max_items = w.attn_items;
+    ap.multi = pl::attention_multi_list(w.attn_work, n, e->attn_max_chunks); ap.max_multi = w.attn_multi;
     if (prefill && l + 1 == c.n_layers) break;
-    mark(e, CAT_OTHER, true);
+    if (timed) mark(e, CAT_OTHER, true);
     rc |= pl::launch_attention(ap, s);
-    mark(e, CAT_ATTN, true);
-    rc |= pl::launch_gemm(e->attn_out, w.w_o, e->parts, n, d, qd, 0, e->sp_o, s);
-    mark(e, CAT_GEMM);
-    rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_o, w.g2, e->a, n, d, c.rms_eps, s);
-    mark(e, CAT_OTHER);
-    rc |= pl::launch_gemm(e->a, w.w_gu, e->mid, n, 2 * c.d_ffn, d, 1, 1, s);
-    rc |= pl::launch_gemm(e->mid, w.w_d, e->parts, n, d, c.d_ffn, 0, e->sp_d, s);
-    mark(e, CAT_GEMM);
+    if (timed) mark(e, CAT_ATTN, true);
+    rc |= pl::launch_gemm(w.attn_out, lw.w_o, w.parts, n, d, qd, 0, e->sp_o, s);
+    if (timed) mark(e, CAT_GEMM);
+    rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->sp_o, lw.g2, w.a, n, d, c.rms_eps, s);
+    if (timed) mark(e, CAT_OTHER);
+    rc |= pl::launch_gemm(w.a, lw.w_gu, w.mid, n, 2 * c.d_ffn, d, 1, 1, s);
+    rc |= pl::launch_gemm(w.mid, lw.w_d, w.parts, n, d, c.d_ffn, 0, e->sp_d, s);
+    if (timed) mark(e, CAT_GEMM);
     const bf16_t *g_next = (l + 1 < c.n_layers) ? layer_weights(e, l + 1).g1 : gf;
-    rc |= pl::launch_resid_rmsnorm(e->h, e->parts, e->sp_d, g_next, e->a, n, d, c.rms_eps, s);
+    rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->sp_d, g_next, w.a, n, d, c.rms_eps, s);
   }
-  mark(e, CAT_OTHER);
   if (prefill) return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
-  rc |= pl::launch_gemm(e->a, lm, e->logits, n, c.vocab, d, 0, 1, s);
+  mark(e, CAT_OTHER);
+  rc |= pl::launch_gemm(w.a, lm, e->logits, n, c.vocab, d, 0, 1, s);
   mark(e, CAT_GEMM);
   pl::SampleParams sp{};
-  sp.logits = e->logits; sp.n = n; sp.vocab = c.vocab; sp.seq_id = e->m_seq_id(true);
-  sp.position = e->m_pos(true); sp.inv_t = e->m_inv_t(true); sp.forced = e->m_forced(true);
+  sp.logits = e->logits; sp.n = n; sp.vocab = c.vocab; sp.seq_id = w.m_seq_id(true);
+  sp.position = w.m_pos(true); sp.inv_t = w.m_inv_t(true); sp.forced = w.m_forced(true);
   sp.seed = c.seed; sp.token = e->tok_d; sp.logprob = e->lp_d; sp.workspace = e->samp_ws;
   sp.last_tok = nullptr; sp.row_slot = nullptr;
   rc |= pl::launch_sample(sp, s);
@@ -415,61 +467,96 @@ int admit(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_t n_prompt
   return PL_OK;
 }
 
+// Add the GPU time of finished cache-only passes to the counters they belong to.
+void harvest_passes(pl_engine *e) {
+  for (auto &im : e->ring) {
+    if (!im.pending || hipEventQuery(im.ev_end) != hipSuccess) continue;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, im.ev_begin, im.ev_end) == hipSuccess && im.ms_into) *im.ms_into += ms;
+    im.pending = false;
+  }
+  (void)hipGetLastError();
+}
+
+// Wait for every cache-only pass enqueued so far; slots whose prompts were being read join the batch.
+int drain_passes(pl_engine *e) {
+  if (e->dry) {
+    for (Seq &q : e->seqs) q.reading = false;
+    return PL_OK;
+  }
+  if (e->pre_pending) {
+    HIP_TRY(hipStreamSynchronize(e->wk[1].stream));
+    e->pre_pending = false;
+  }
+  harvest_passes(e);
+  for (Seq &q : e->seqs) q.reading = false;
+  return PL_OK;
+}
+
 // Cache-only passes: rows (slot, position, token) go through the decode kernels in prefill mode, in
-// groups of up to 256; the rows of one slot must come in position order, because a
-// row attends to the keys and values that earlier rows of its slot (in this or an earlier group) leave.
+// groups of up to 256, on the second work set's stream; the rows of one slot must come in position
+// order, because a row attends to the keys and values that earlier rows of its slot (in this or an
+// earlier group) leave.  Returns once everything is enqueued; the caller waits (or records an event).
 int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::vector<int32_t> &positions,
                   const std::vector<int32_t> &tokens, double *ms_total, uint64_t *passes) {
   const pl_model_cfg &c = e->cfg;
   const int rows_max = 256;
-  int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
-  float *inv_t = e->m_inv_t(false);
-  uint64_t *sid = e->m_seq_id(false);
+  pl_engine::Work &w = e->wk[1];
   if (!e->dry) HIP_TRY(hipSetDevice(c.device));
   const size_t total = slots.size();
   for (size_t r0 = 0; r0 < total; r0 += rows_max) {
     const int n = (int)std::min<size_t>(rows_max, total - r0);
-    int items = 0, multi = 0;
-    for (int r = 0; r < n; ++r) {
-      const Seq &q = e->seqs[slots[r0 + r]];
-      row_slot[r] = slots[r0 + r];
-      pos[r] = positions[r0 + r];
-      inp[r] = tokens[r0 + r];
-      frc[r] = -1;
-      inv_t[r] = q.inv_t;
-      sid[r] = q.seq_id;
-      items += (pos[r] + 1 + e->attn_chunk - 1) / e->attn_chunk;
-      multi += pos[r] + 1 > e->attn_chunk;
-    }
-    e->attn_items = items;
-    e->attn_multi = multi;
     if (!e->dry) {
-      hipStream_t s = e->s_dec;
-      if (e->pt_dirty) {
-        HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
-        e->pt_dirty = false;
+      // next host image of the ring; if its previous pass has not run yet, wait for it
+      pl_engine::PassImage &im = e->ring[e->ring_next];
+      e->ring_next = (e->ring_next + 1) % e->ring.size();
+      if (im.pending) {
+        HIP_TRY(hipEventSynchronize(im.ev_end));
+        harvest_passes(e);
       }
-      HIP_TRY(hipMemcpyAsync(e->meta_d, e->meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
-      HIP_TRY(hipEventRecord(e->ev_a, s));
-      const int prof = e->profile;
-      e->profile = 0;   // the per-group timers describe decode steps only
-      int rc = enqueue_step(e, n, true);
-      e->profile = prof;
+      w.meta_h = im.meta_h;
+      int items = 0, multi = 0;
+      int32_t *row_slot = w.m_row_slot(false), *pos = w.m_pos(false), *inp = w.m_input(false), *frc = w.m_forced(false);
+      float *inv_t = w.m_inv_t(false);
+      uint64_t *sid = w.m_seq_id(false);
+      for (int r = 0; r < n; ++r) {
+        const Seq &q = e->seqs[slots[r0 + r]];
+        row_slot[r] = slots[r0 + r];
+        pos[r] = positions[r0 + r];
+        inp[r] = tokens[r0 + r];
+        frc[r] = -1;
+        inv_t[r] = q.inv_t;
+        sid[r] = q.seq_id;
+        items += (pos[r] + 1 + e->attn_chunk - 1) / e->attn_chunk;
+        multi += pos[r] + 1 > e->attn_chunk;
+      }
+      w.attn_items = items;
+      w.attn_multi = multi;
+      hipStream_t s = w.stream;
+      // The page table goes up on this stream too (the same bytes a decode step would send: the host
+      // table is the truth); the dirty flag stays, the decode stream sends its own copy.
+      if (r0 == 0)
+        HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
+      HIP_TRY(hipEventRecord(im.ev_begin, s));
+      int rc = enqueue_step(e, w, n, true);
       if (rc) return rc;
-      HIP_TRY(hipEventRecord(e->ev_b, s));
-      HIP_TRY(hipStreamSynchronize(s));   // the host metadata image is reused by the next group
-      float ms = 0.f;
-      HIP_TRY(hipEventElapsedTime(&ms, e->ev_a, e->ev_b));
-      *ms_total += ms;
+      HIP_TRY(hipEventRecord(im.ev_end, s));
+      im.pending = true;
+      im.ms_into = ms_total;
+      e->pre_pending = true;
     }
     ++*passes;
   }
+  if (!e->dry && total) HIP_TRY(hipEventRecord(e->ev_pre_last, w.stream));
   return PL_OK;
 }
 
 // "KV cache recomputed" variant of Sec. 5.1: after a flip, replay every token each sequence has read
 // so far under the new weights, overwriting its cached keys and values in place.
 int recompute_all_kv(pl_engine *e) {
+  int rc = drain_passes(e);   // prompts still being read in the background finish first
+  if (rc) return rc;
   std::vector<int32_t> slots, positions, tokens;
   for (int s = 0; s < e->cfg.max_batch; ++s) {
     const Seq &q = e->seqs[s];
@@ -480,8 +567,9 @@ int recompute_all_kv(pl_engine *e) {
       tokens.push_back(q.hist[p]);
     }
   }
-  int rc = run_kv_passes(e, slots, positions, tokens, &e->st.recompute_ms, &e->st.recompute_passes);
+  rc = run_kv_passes(e, slots, positions, tokens, &e->st.recompute_ms, &e->st.recompute_passes);
   if (rc) return rc;
+  if ((rc = drain_passes(e))) return rc;
   e->st.recompute_positions += slots.size();
   return PL_OK;
 }
@@ -522,9 +610,10 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
   set_pool_pages(e, n_pages);
   e->rows_cap = std::max(cfg->max_batch, 256);
   e->meta_bytes = (int64_t)e->rows_cap * (4 * 5 + 8);
+  e->wk[0].rows_cap = e->wk[1].rows_cap = e->rows_cap;
   if (e->dry) {
-    e->meta_h = (char *)calloc(1, (size_t)e->meta_bytes);
-    if (!e->meta_h) { delete e; return fail(PL_E_NOMEM, "out of host memory"); }
+    e->wk[0].meta_h = (char *)calloc(1, (size_t)e->meta_bytes);
+    if (!e->wk[0].meta_h) { delete e; return fail(PL_E_NOMEM, "out of host memory"); }
   } else {
     if (cfg->device < 0) { delete e; return fail(PL_E_INVAL, "bad device"); }
     rc = alloc_device(e);
@@ -537,25 +626,35 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
 void pl_destroy(pl_engine *e) {
   if (!e) return;
   if (e->dry) {
-    free(e->meta_h);
+    free(e->wk[0].meta_h);
   } else {
     (void)hipSetDevice(e->cfg.device);
     if (e->s_dec) (void)hipStreamSynchronize(e->s_dec);
     if (e->s_copy) (void)hipStreamSynchronize(e->s_copy);
-    void *dev[] = {e->wbuf[0], e->wbuf[1], e->kv_pool, e->pt_d, e->meta_d, e->h, e->a, e->parts, e->q_rot,
-                   e->attn_out, e->mid, e->logits, e->cs, e->ctx_len, e->tok_d, e->lp_d, e->attn_po,
-                   e->attn_pml, e->samp_ws, e->attn_work};
+    if (e->wk[1].stream) (void)hipStreamSynchronize(e->wk[1].stream);
+    void *dev[] = {e->wbuf[0], e->wbuf[1], e->kv_pool, e->pt_d, e->logits, e->tok_d, e->lp_d, e->samp_ws};
     for (void *p : dev)
       if (p) (void)hipFree(p);
-    void *hst[] = {e->pt_h, e->meta_h, e->tok_h, e->lp_h};
+    void *hst[] = {e->pt_h, e->wk[0].meta_h, e->tok_h, e->lp_h};
     for (void *p : hst)
       if (p) (void)hipHostFree(p);
+    hipStream_t s_pre = e->wk[1].stream;
+    free_work(e->wk[0]);
+    free_work(e->wk[1]);
+    for (auto &im : e->ring) {
+      if (im.meta_h) (void)hipHostFree(im.meta_h);
+      if (im.ev_begin) (void)hipEventDestroy(im.ev_begin);
+      if (im.ev_end) (void)hipEventDestroy(im.ev_end);
+    }
+    for (hipEvent_t ev : e->ev_slot)
+      if (ev) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : e->prof_ev) (void)hipEventDestroy(ev);
-    hipEvent_t evs[] = {e->ev_a, e->ev_b, e->ev_c, e->ev_staged, e->ev_copy0};
+    hipEvent_t evs[] = {e->ev_a, e->ev_b, e->ev_c, e->ev_staged, e->ev_copy0, e->ev_pre_last};
     for (hipEvent_t ev : evs)
       if (ev) (void)hipEventDestroy(ev);
     if (e->s_dec) (void)hipStreamDestroy(e->s_dec);
     if (e->s_copy) (void)hipStreamDestroy(e->s_copy);
+    if (s_pre) (void)hipStreamDestroy(s_pre);
   }
   delete e;
 }
@@ -627,6 +726,7 @@ int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes) {
   if (!e->dry) {
     HIP_TRY(hipSetDevice(e->cfg.device));
     HIP_TRY(hipStreamSynchronize(e->s_dec));
+    HIP_TRY(hipStreamSynchronize(e->wk[1].stream));   // a prompt read in the background finishes under the old weights
     HIP_TRY(hipMemcpy(e->wbuf[e->active_buf], src, (size_t)nbytes, hipMemcpyDefault));
   }
   if (e->loaded) { e->version++; e->st.swaps++; }
@@ -649,11 +749,14 @@ int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flag
   if (!e->dry) {
     HIP_TRY(hipSetDevice(e->cfg.device));
     if (e->cfg.n_weight_buffers == 2) {
-      // Steps are synchronous, so no kernel is reading the inactive buffer now.
+      // Steps are synchronous, so no decode kernel is reading the inactive buffer now; a prompt being
+      // read in the background may still be (it started before the last flip): the copy waits for it.
+      if (e->pre_pending) HIP_TRY(hipStreamWaitEvent(e->s_copy, e->ev_pre_last, 0));
       HIP_TRY(hipEventRecord(e->ev_copy0, e->s_copy));
       HIP_TRY(hipMemcpyAsync(e->wbuf[e->active_buf ^ 1], src, (size_t)nbytes, hipMemcpyDefault, e->s_copy));
       HIP_TRY(hipEventRecord(e->ev_staged, e->s_copy));
     } else {
+      HIP_TRY(hipStreamSynchronize(e->wk[1].stream));
       HIP_TRY(hipEventRecord(e->ev_copy0, e->s_dec));
       HIP_TRY(hipMemcpyAsync(e->wbuf[0], src, (size_t)nbytes, hipMemcpyDefault, e->s_dec));
       HIP_TRY(hipEventRecord(e->ev_staged, e->s_dec));
@@ -711,6 +814,10 @@ int pl_retire_sequence(pl_engine *e, int32_t slot) {
   if (!e || slot < 0 || slot >= e->cfg.max_batch) return fail(PL_E_INVAL, "slot out of range");
   Seq &q = e->seqs[slot];
   if (!q.active) return fail(PL_E_STATE, "slot %d is idle", slot);
+  if (q.reading && !e->dry) {   // its pages are still being written
+    HIP_TRY(hipSetDevice(e->cfg.device));
+    HIP_TRY(hipEventSynchronize(e->ev_slot[slot]));
+  }
   for (int32_t p : q.pages) e->free_pages.push_back(p);
   q = Seq{};
   return PL_OK;
@@ -728,11 +835,43 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   if (!e->loaded) return fail(PL_E_STATE, "no weights loaded");
   const pl_model_cfg &c = e->cfg;
   // 1. validate: nothing below may fail half-way
+  // an update that rebuilds the caches may become active in this step: background reading ends first
+  if (e->staged && e->staged_recompute) {
+    int rc = drain_passes(e);
+    if (rc) return rc;
+  }
+  // slots whose prompt is being read in the background join the batch once that is done; if nothing
+  // else is in flight the step waits for the first of them instead of returning empty-handed
+  int n_reading = 0, n_ready = 0;
+  for (int s = 0; s < c.max_batch; ++s) {
+    Seq &q = e->seqs[s];
+    if (!q.active) continue;
+    if (q.reading) {
+      if (e->dry) q.reading = false;
+      else {
+        hipError_t qy = hipEventQuery(e->ev_slot[s]);
+        if (qy == hipSuccess) q.reading = false;
+        else if (qy != hipErrorNotReady) return fail(PL_E_HIP, "hipEventQuery: %s", hipGetErrorString(qy));
+      }
+    }
+    if (q.reading) ++n_reading; else ++n_ready;
+  }
+  if (n_reading && !n_ready) {
+    for (int s = 0; s < c.max_batch; ++s) {
+      Seq &q = e->seqs[s];
+      if (!q.active || !q.reading) continue;
+      HIP_TRY(hipSetDevice(c.device));
+      HIP_TRY(hipEventSynchronize(e->ev_slot[s]));   // slots were enqueued in this order on one stream
+      q.reading = false;
+      break;
+    }
+  }
+  if (!e->dry && !n_reading && e->pre_pending && hipEventQuery(e->ev_pre_last) == hipSuccess) e->pre_pending = false;
   int n = 0;
   int64_t new_pages = 0;
   for (int s = 0; s < c.max_batch; ++s) {
     const Seq &q = e->seqs[s];
-    if (!q.active) continue;
+    if (!q.active || q.reading) continue;
     if (q.n_emitted >= q.max_new) return fail(PL_E_STATE, "slot %d has finished; retire it", s);
     if (q.pos >= c.max_context) return fail(PL_E_CTX, "slot %d is at max_context", s);
     if (forced && forced[s] >= c.vocab) return fail(PL_E_INVAL, "forced token out of range");
@@ -794,15 +933,16 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   }
 
   // 3. pages and per-step metadata
-  int32_t *row_slot = e->m_row_slot(false), *pos = e->m_pos(false), *inp = e->m_input(false), *frc = e->m_forced(false);
-  float *inv_t = e->m_inv_t(false);
-  uint64_t *sid = e->m_seq_id(false);
+  pl_engine::Work &w = e->wk[0];
+  int32_t *row_slot = w.m_row_slot(false), *pos = w.m_pos(false), *inp = w.m_input(false), *frc = w.m_forced(false);
+  float *inv_t = w.m_inv_t(false);
+  uint64_t *sid = w.m_seq_id(false);
   int r = 0;
   double kv_tokens = 0;
   int items = 0, multi = 0;
   for (int s = 0; s < c.max_batch; ++s) {
     Seq &q = e->seqs[s];
-    if (!q.active) continue;
+    if (!q.active || q.reading) continue;
     if (q.pos / e->page_tokens >= (int)q.pages.size()) {
       q.pages.push_back(e->free_pages.back());
       e->free_pages.pop_back();
@@ -822,8 +962,8 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     ++r;
   }
 
-  e->attn_items = items;
-  e->attn_multi = multi;
+  w.attn_items = items;
+  w.attn_multi = multi;
 
   // 4. run
   if (!e->dry) {
@@ -833,9 +973,9 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
       e->pt_dirty = false;
     }
-    HIP_TRY(hipMemcpyAsync(e->meta_d, e->meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
     HIP_TRY(hipEventRecord(e->ev_a, s));
-    int rc = enqueue_step(e, n);
+    int rc = enqueue_step(e, w, n);
     if (rc) return rc;
     HIP_TRY(hipEventRecord(e->ev_b, s));
     HIP_TRY(hipMemcpyAsync(e->tok_h, e->tok_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
@@ -864,7 +1004,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   r = 0;
   for (int s = 0; s < c.max_batch; ++s) {
     Seq &q = e->seqs[s];
-    if (!q.active) continue;
+    if (!q.active || q.reading) continue;
     const int32_t tok = e->dry ? (frc[r] >= 0 ? frc[r] : -1) : e->tok_h[r];
     const float lp = e->dry ? NAN : e->lp_h[r];
     const bool emitted = q.pos >= q.n_prompt - 1;
@@ -890,13 +1030,15 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   return PL_OK;
 }
 
-int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
-  if (!e) return fail(PL_E_INVAL, "NULL argument");
+// Enqueue the reading of a slot's prompt (all positions not read yet, except the last) on the
+// cache-only stream; the slot is marked as reading and its event recorded.
+static int start_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
   if (out_positions) *out_positions = 0;
   if (!e->loaded) return fail(PL_E_STATE, "no weights loaded");
   const pl_model_cfg &c = e->cfg;
   if (slot < 0 || slot >= c.max_batch || !e->seqs[slot].active) return fail(PL_E_STATE, "slot %d is idle", slot);
   Seq &q = e->seqs[slot];
+  if (q.reading) return fail(PL_E_BUSY, "slot %d is already reading its prompt", slot);
   const int first = q.pos, last = q.n_prompt - 1;   // positions [first, last) are read here
   if (first >= last) return PL_OK;
   if ((int)q.prompt.size() < q.n_prompt) return fail(PL_E_STATE, "slot %d holds no prompt", slot);
@@ -905,16 +1047,39 @@ int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
   for (int p = first; p < last; ++p) { positions.push_back(p); tokens.push_back(q.prompt[p]); }
   int rc = run_kv_passes(e, slots, positions, tokens, &e->st.prefill_ms, &e->st.prefill_passes);
   if (rc) return rc;
+  if (!e->dry) HIP_TRY(hipEventRecord(e->ev_slot[slot], e->wk[1].stream));
   e->st.prefill_positions += last - first;
   if (q.hist_known) q.hist.insert(q.hist.end(), tokens.begin(), tokens.end());
   q.pos = last;
-  e->last_n = 0;
+  q.reading = true;
   if (out_positions) *out_positions = last - first;
   return PL_OK;
 }
 
+int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  int rc = start_prefill(e, slot, out_positions);
+  if (rc) return rc;
+  Seq &q = e->seqs[slot];
+  if (q.reading) {
+    if (!e->dry) {
+      HIP_TRY(hipEventSynchronize(e->ev_slot[slot]));
+      harvest_passes(e);
+    }
+    q.reading = false;
+  }
+  e->last_n = 0;
+  return PL_OK;
+}
+
+int pl_prefill_async(pl_engine *e, int32_t slot, int32_t *out_positions) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  return start_prefill(e, slot, out_positions);
+}
+
 int pl_get_stats(pl_engine *e, pl_stats *out) {
   if (!e || !out) return fail(PL_E_INVAL, "NULL argument");
+  if (!e->dry) harvest_passes(e);
   e->st.active_version = e->version;
   e->st.kv_pages_free = (int64_t)e->free_pages.size();
   *out = e->st;
@@ -941,6 +1106,7 @@ static int kv_xfer(pl_engine *e, int32_t slot, int32_t layer, float *k, float *v
   if (n_ctx < 0 || (int64_t)n_ctx > (int64_t)q.pages.size() * e->page_tokens) return fail(PL_E_INVAL, "n_ctx exceeds the slot's pages");
   HIP_TRY(hipSetDevice(c.device));
   HIP_TRY(hipStreamSynchronize(e->s_dec));
+  HIP_TRY(hipStreamSynchronize(e->wk[1].stream));
   const int hd = c.head_dim, Hkv = c.n_kv_heads, ptok = e->page_tokens;
   std::vector<uint16_t> img((size_t)e->page_stride);
   for (int p0 = 0; p0 < n_ctx; p0 += ptok) {

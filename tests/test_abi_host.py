@@ -314,3 +314,21 @@ def test_recomputation_is_refused_at_the_flip_if_a_slot_lost_its_history_meanwhi
     e.debug_set_history(s1, np.arange(20))
     r = e.decode_step()
     assert r["weight_version"].tolist() == [1, 1] and e.stats()["recompute_positions"] == 1 + 20
+
+
+def test_background_prompt_reading_bookkeeping():
+    e = _loaded()
+    s0 = e.add_sequence(1, [5, 6, 7, 8, 9, 10, 11], 10)
+    s1 = e.add_sequence(2, [4, 5], 3)
+    assert e.prefill_async(s0) == 6
+    with pytest.raises(pl.PlError) as ex:
+        e.prefill_async(s0)
+    assert ex.value.code == pl.PL_E_BUSY
+    assert e.stats()["prefill_positions"] == 6 and e.stats()["steps"] == 0
+    r = e.decode_step()                       # a bookkeeping engine finishes the reading at once
+    assert r["n"] == 2 and r["position"].tolist() == [6, 0] and r["emitted"].tolist() == [1, 0]
+    s2 = e.add_sequence(3, list(range(10, 30)), 2)
+    assert e.prefill_async(s2) == 19
+    e.retire_sequence(s2)                     # retiring a slot that is still reading is allowed
+    assert e.num_active() == 2
+    assert e.prefill_async(s1) == 0           # nothing left to read

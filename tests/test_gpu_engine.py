@@ -542,3 +542,111 @@ def test_prefill_of_a_partly_read_prompt_and_of_neighbours_in_other_states(weigh
     for _ in range(8):
         both_step()
     eng.close()
+
+
+# ---- prompt reading in the background (Alg. 2 refill that does not stall the batch) ------------------
+
+def test_background_prompt_reading_equals_the_blocking_one_and_the_oracle(weights):
+    """pl_prefill_async: the refilled slot reads its prompt on a stream of its own while the other slots
+    keep decoding, and joins the batch when done.  Unique: the cache it leaves is bit-identical to
+    pl_prefill's, and from then on the sequence's logits are bit-identical to those of the same sequence
+    in an engine that read the prompt the blocking way.  Against the oracle: per-position logits of the
+    background-read sequence (a sequence's results do not depend on the step at which it joins)."""
+    master, _ = weights
+    n_prompt = 90
+    prompts = synth.random_prompts(np.random.default_rng(31), 2, n_prompt, M.vocab)
+    forced_tokens = np.random.default_rng(32).integers(0, M.vocab, 400).astype(np.int32)   # by position
+    blob = None
+    runs = {}
+    for mode in ("blocking", "background"):
+        eng = _engine(max_batch=4, max_context=256, kv_pool_tokens=4 * 256)
+        blob = eng.pack_weights(master, synth.f32_to_bf16_bits)
+        eng.load_weights(blob)
+        eng.add_sequence(500, prompts[0][:5], 150)             # a neighbour that is decoding all along
+        slot = eng.add_sequence(501, prompts[1], 40)
+        if mode == "blocking":
+            assert eng.prefill(slot) == n_prompt - 1
+        else:
+            assert eng.prefill_async(slot) == n_prompt - 1
+            with pytest.raises(pl.PlError) as ex:
+                eng.prefill_async(slot)
+            assert ex.value.code == pl.PL_E_BUSY
+        logits_by_pos, joined_at = {}, None
+        for step in range(60):
+            # the sequence is forced to the token drawn for the position it is about to read (ignored while
+            # it is still reading its prompt), so both runs and the oracle feed it identical inputs
+            forced = np.full(4, -1, np.int32)
+            forced[0] = forced_tokens[step + 200]
+            forced[slot] = forced_tokens[n_prompt - 1 + len(logits_by_pos)]
+            out = eng.decode_step(forced)
+            rows = {int(s): i for i, s in enumerate(out["slot"])}
+            if slot in rows:
+                if joined_at is None:
+                    joined_at = step
+                    kv = [eng.debug_read_kv(slot, l, n_prompt - 1) for l in range(M.n_layers)]
+                i = rows[slot]
+                assert out["position"][i] == n_prompt - 1 + len(logits_by_pos)
+                logits_by_pos[int(out["position"][i])] = eng.debug_get_logits(out["n"])[i].copy()
+            if len(logits_by_pos) >= 12:
+                break
+        assert joined_at is not None and len(logits_by_pos) >= 12
+        assert eng.stats()["prefill_positions"] == n_prompt - 1 and eng.stats()["prefill_ms"] > 0
+        runs[mode] = (kv, logits_by_pos, joined_at)
+        eng.close()
+    kv_a, lg_a, _ = runs["blocking"]
+    kv_b, lg_b, joined = runs["background"]
+    print("background reading joined the batch at step", joined)
+    for l in range(M.n_layers):
+        assert np.array_equal(kv_a[l][0], kv_b[l][0]) and np.array_equal(kv_a[l][1], kv_b[l][1])
+    common = sorted(set(lg_a) & set(lg_b))
+    assert len(common) >= 12
+    for p in common:
+        assert np.array_equal(lg_a[p], lg_b[p]), p
+    # the oracle reads the same tokens, one per step
+    orc = OracleEngine(M, _rounded(master), max_batch=1, seed=SEED)
+    orc.add_sequence(501, prompts[1], 40)
+    for p in range(max(common) + 1):
+        f = None if p < n_prompt - 1 else np.array([forced_tokens[p]], np.int32)
+        orc.decode_step(f)
+        if p in lg_b:
+            ok, err = close(lg_b[p], orc.last_logits[0], ATOL, RTOL)
+            assert ok, (p, err)
+
+
+def test_background_prompt_reading_across_an_update_and_a_retire(weights):
+    """The prompt is read under the weights active when the reading was requested, even if an update
+    becomes active before it ends; retiring a slot that is still reading waits for its passes."""
+    master, pert = weights
+    prompts = synth.random_prompts(np.random.default_rng(33), 2, 70, M.vocab)
+    eng = _engine(max_batch=4, max_context=256, kv_pool_tokens=4 * 256)
+    blobs = [eng.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
+    eng.load_weights(blobs[0])
+    ref = _engine(max_batch=4, max_context=256, kv_pool_tokens=4 * 256)
+    ref.load_weights(blobs[0])
+    for e in (eng, ref):
+        e.add_sequence(1, prompts[0][:4], 100)
+    a = eng.add_sequence(2, prompts[1], 20)
+    eng.prefill_async(a)
+    eng.swap_weights(blobs[1], flags=pl.PL_SWAP_WAIT)          # becomes active at the next step
+    out = eng.decode_step()
+    assert out["weight_version"][0] == 1
+    for _ in range(40):
+        out = eng.decode_step()
+        if a in out["slot"].tolist():
+            break
+    assert a in out["slot"].tolist()
+    b = ref.add_sequence(2, prompts[1], 20)
+    ref.prefill(b)                                             # under the old weights, blocking
+    for l in range(M.n_layers):
+        ka, va = eng.debug_read_kv(a, l, 69)
+        kb, vb = ref.debug_read_kv(b, l, 69)
+        assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    # a second update while a new slot is reading, then retire that slot at once
+    c = eng.add_sequence(3, prompts[0], 20)
+    eng.prefill_async(c)
+    eng.swap_weights(blobs[0], flags=pl.PL_SWAP_ASYNC)
+    eng.retire_sequence(c)
+    for _ in range(5):
+        out = eng.decode_step()
+        assert np.isfinite(eng.debug_get_logits(out["n"])).all()
+    eng.close(); ref.close()
