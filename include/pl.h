@@ -304,6 +304,18 @@ int pl_sample(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq
               const int32_t *position, const float *inv_temperature, const int32_t *forced,
               uint64_t seed, int32_t *token, float *logprob, void *workspace, void *stream);
 
+/* pl_sample for callers that cannot allocate or carry a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments and results as pl_sample, but the
+ * per-slice partial results live in a 256 KiB array in the library's own device image (one copy per
+ * GPU, held until the process ends), so the call allocates nothing and takes no workspace.  Limits:
+ * n <= 512 rows and vocab <= 262144; beyond them PL_E_INVAL and nothing is launched.  All calls on one
+ * GPU share that array: calls that overlap in time on the same GPU (different streams or threads) race
+ * and must be serialised by the caller; nothing needs clearing between calls (every partial a launch
+ * reads was written by that launch). */
+int pl_sample_static(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq_id,
+                     const int32_t *position, const float *inv_temperature, const int32_t *forced,
+                     uint64_t seed, int32_t *token, float *logprob, void *stream);
+
 /* Trainer-side use of the recorded log-probs (Sec. 2.1): truncated token-level importance weights
  * w_i = min(c, exp(logp_pi[i] - logp_mu[i])) (the paper clamps at c = 5) and the normalised effective
  * sample size (sum w)^2 / (N sum w^2) (Sec. 2.1, ESS), per sequence of a packed batch and over all its

@@ -10,7 +10,7 @@ __all__ = [
     "PL_OK", "PL_E_INVAL", "PL_E_NOSLOT", "PL_E_NOKV", "PL_E_BUSY", "PL_E_STATE", "PL_E_CTX", "PL_E_HIP",
     "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_SWAP_RECOMPUTE_KV", "PL_DEVICE_NONE", "PlError", "ModelCfg", "StepOut", "Stats",
     "lib", "library_path", "Engine", "operand_order", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
-    "pl_gemm_bf16", "pl_sample", "pl_sample_workspace_bytes", "pl_debug_stream_read", "pl_is_ess", "EXPORTS",
+    "pl_gemm_bf16", "pl_sample", "pl_sample_static", "pl_sample_workspace_bytes", "pl_debug_stream_read", "pl_is_ess", "EXPORTS",
 ]
 
 PL_OK, PL_E_INVAL, PL_E_NOSLOT, PL_E_NOKV, PL_E_BUSY, PL_E_STATE, PL_E_CTX, PL_E_HIP, PL_E_NOMEM = 0, -1, -2, -3, -4, -5, -6, -7, -8
@@ -23,7 +23,7 @@ EXPORTS = [
     "pl_pack_weights", "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_prefill_async", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
     "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
-    "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample", "pl_is_ess",
+    "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample", "pl_sample_static", "pl_is_ess",
 ]
 
 
@@ -112,6 +112,7 @@ def lib():
         "pl_gemm_bf16": (C.c_int, [vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "pl_sample_workspace_bytes": (i64, [i32, i32]),
         "pl_sample": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, u64, vp, vp, vp, vp]),
+        "pl_sample_static": (C.c_int, [vp, i32, i32, vp, vp, vp, vp, u64, vp, vp, vp]),
         "pl_is_ess": (C.c_int, [vp, vp, vp, i32, f32, vp, vp, vp, vp, vp]),
     }
     for name, (res, args) in sigs.items():
@@ -386,6 +387,10 @@ def pl_sample_workspace_bytes(n, vocab):
 def pl_sample(logits, n, vocab, seq_id, position, inv_temperature, forced, seed, token, logprob, workspace, stream=0):
     _check(lib().pl_sample(logits, n, vocab, seq_id, position, inv_temperature, forced, seed, token, logprob,
                            workspace, stream))
+
+
+def pl_sample_static(logits, n, vocab, seq_id, position, inv_temperature, forced, seed, token, logprob, stream=0):
+    _check(lib().pl_sample_static(logits, n, vocab, seq_id, position, inv_temperature, forced, seed, token, logprob, stream))
 
 
 def pl_is_ess(logp_pi, logp_mu, seq_offsets, n_seq, c, w_out, seq_sums, ess_seq, totals, stream=0):

@@ -13,6 +13,8 @@
 // One pass over the logits: every workgroup scans a slice of one row keeping (max z, sum exp,
 // best y, its index); a second small kernel merges the slices of a row in slice order.
 #include "pl_common.h"
+
+#include <mutex>
 #pragma clang fp contract(off)
 
 namespace pl {
@@ -144,6 +146,37 @@ __global__ void sample_merge_kernel(SampleParams p, int nslice) {
 }
 
 }  // namespace
+
+// ---- slice partials kept in the library's own device memory, for callers that cannot allocate ------
+namespace {
+constexpr int STATIC_MAX_ROWS = 512, STATIC_MAX_VOCAB = 262144;
+constexpr int64_t STATIC_SCRATCH_BYTES = (int64_t)STATIC_MAX_ROWS * (STATIC_MAX_VOCAB / SLICE) * (int64_t)sizeof(Part);   // 256 KiB
+// One copy per GPU the library runs on, held until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress: the address kernels use is looked up once per device below.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mu;
+}  // namespace
+
+// Device address of the current device's scratch array (looked up on the first call on that device)
+// and the largest launch it serves.  Returns 0, -1 if the shape does not fit, -7 on a HIP error.
+int sample_static_workspace(int n, int vocab, void **ptr) {
+  if (n < 1 || n > STATIC_MAX_ROWS || vocab < 1 || vocab > STATIC_MAX_VOCAB ||
+      sample_workspace_bytes(n, vocab) > STATIC_SCRATCH_BYTES)
+    return -1;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return -7;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return -7;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return 0;
+}
+void sample_static_limits(int *max_rows, int *max_vocab) { *max_rows = STATIC_MAX_ROWS; *max_vocab = STATIC_MAX_VOCAB; }
 
 int64_t sample_workspace_bytes(int n, int vocab) {
   return (int64_t)n * ((vocab + SLICE - 1) / SLICE) * (int64_t)sizeof(Part);

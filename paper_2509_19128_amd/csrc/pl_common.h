@@ -61,6 +61,8 @@ struct SampleParams {
 };
 int64_t sample_workspace_bytes(int n, int vocab);
 int launch_sample(const SampleParams &p, hipStream_t s);
+int sample_static_workspace(int n, int vocab, void **ptr);
+void sample_static_limits(int *max_rows, int *max_vocab);
 
 // per-step metadata, one row per occupied slot (device copies of host arrays)
 struct StepMeta {

@@ -1264,4 +1264,24 @@ int pl_sample(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq
   return PL_OK;
 }
 
+int pl_sample_static(const float *logits, int32_t n, int32_t vocab, const uint64_t *seq_id, const int32_t *position,
+                     const float *inv_temperature, const int32_t *forced, uint64_t seed, int32_t *token, float *logprob,
+                     void *stream) {
+  if (!logits || !seq_id || !position || !inv_temperature || !token || !logprob) return fail(PL_E_INVAL, "NULL argument");
+  if (n < 1 || vocab < 4 || vocab % 4) return fail(PL_E_INVAL, "need n >= 1 and vocab a positive multiple of 4");
+  void *ws = nullptr;
+  const int rc = pl::sample_static_workspace(n, vocab, &ws);
+  if (rc == -1) {
+    int mr = 0, mv = 0;
+    pl::sample_static_limits(&mr, &mv);
+    return fail(PL_E_INVAL, "pl_sample_static serves at most %d rows and a vocabulary of %d; got n = %d, vocab = %d", mr, mv, n, vocab);
+  }
+  if (rc) return fail(PL_E_HIP, "hipGetSymbolAddress of the sampler's scratch array failed");
+  pl::SampleParams p{};
+  p.logits = logits; p.n = n; p.vocab = vocab; p.seq_id = seq_id; p.position = position; p.inv_t = inv_temperature;
+  p.forced = forced; p.seed = seed; p.token = token; p.logprob = logprob; p.workspace = ws;
+  if (pl::launch_sample(p, (hipStream_t)stream)) return fail(PL_E_HIP, "sampler launch failed");
+  return PL_OK;
+}
+
 }  // extern "C"
