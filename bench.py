@@ -647,7 +647,8 @@ def main():
         split = {k: (a1[k] - a0[k]) / 16 for k in ("attn_ms", "gemm_ms", "sample_ms", "other_ms")}
 
     d = {k: s1[k] - s0[k] for k in ("steps", "tokens_emitted", "slot_steps", "gpu_ms_total", "algorithmic_bytes",
-                                     "attn_ms", "gemm_ms", "sample_ms", "other_ms", "attn_launches", "attn_kv_bytes")}
+                                     "attn_ms", "gemm_ms", "sample_ms", "other_ms", "attn_launches", "attn_kv_bytes",
+                                     "attn_shared_ms", "attn_shared_launches", "attn_shared_kv_bytes")}
     sm = np.asarray(step_ms)
     med = float(np.median(sm))
     # swap stall: the step that contains the flip against the median of the 16 surrounding steps (None if no
@@ -697,11 +698,21 @@ def main():
     res["hbm_read_stream_ceiling_GBs"] = stream_ceiling(torch, pl)
     res["hbm_read_stream_ceiling_nontemporal_GBs"] = stream_ceiling(torch, pl, nontemporal=True)
     if d["attn_launches"]:
-        per_launch_bytes = d["attn_kv_bytes"] / d["attn_launches"]
-        per_launch_ms = d["attn_ms"] / d["attn_launches"]
+        # The kernel's figure is taken from the launches that had the GPU to themselves; launches of steps that
+        # shared it with a background prompt-reading pass are reported beside it.
+        alone = d["attn_launches"] - d["attn_shared_launches"]
+        if alone:
+            per_launch_bytes = (d["attn_kv_bytes"] - d["attn_shared_kv_bytes"]) / alone
+            per_launch_ms = (d["attn_ms"] - d["attn_shared_ms"]) / alone
+        else:
+            per_launch_bytes, per_launch_ms = d["attn_kv_bytes"] / d["attn_launches"], d["attn_ms"] / d["attn_launches"]
         ach = per_launch_bytes / per_launch_ms / 1e6
         res["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel (+ merge)", "achieved": ach, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                           "launches": int(alone or d["attn_launches"]),
+                           "launches_beside_a_background_pass": int(d["attn_shared_launches"]),
+                           "achieved_beside_a_background_pass": (d["attn_shared_kv_bytes"] / d["attn_shared_ms"] / 1e6
+                                                                 if d["attn_shared_launches"] else None),
                            # HBM bytes per launch from the rocprofv3 counter runs of this same command
                            # (FETCH_SIZE and WRITE_SIZE, scaled on plain copies), as recorded in profiles/
                            "traffic": counter_traffic(args.workload, per_launch_bytes),

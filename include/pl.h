@@ -97,6 +97,10 @@ typedef struct {
   double attn_ms, gemm_ms, sample_ms, other_ms;
   uint64_t attn_launches, gemm_launches; /* attention launches (one per layer per step), GEMM launches */
   double attn_kv_bytes;                  /* K/V bytes those attention launches had to read */
+  /* the part of the three attention figures above that was measured in steps during which a background
+   * cache-only pass (pl_prefill_async) was in flight, i.e. while the kernel shared the GPU */
+  double attn_shared_ms, attn_shared_kv_bytes;
+  uint64_t attn_shared_launches;
   /* batched prompt reading (pl_prefill); not part of steps / slot_steps / gpu_ms_total above */
   uint64_t prefill_passes, prefill_positions;
   double prefill_ms;
@@ -237,6 +241,10 @@ int pl_debug_set_history(pl_engine *e, int32_t slot, const int32_t *tokens, int3
  * else lands in other_ms); 2 around every group (attention, GEMMs, sampler, rest).  Each event costs a
  * little GPU time between kernels, which is why level 1 exists. */
 int pl_debug_set_profile(pl_engine *e, int32_t level);
+/* A decode step replays its kernel sequence from a captured HIP graph (one per launch shape; on by
+ * default, not used while pl_debug_set_profile is on).  on = 0 makes every step launch its kernels one
+ * by one instead; results are identical either way. */
+int pl_debug_set_graphs(pl_engine *e, int32_t on);
 /* Debugging aid for the double-buffered update: when on, the step that flips to the new weights
  * first fills the buffer that just went inactive with bf16 NaN, so any kernel that still reads the
  * old weights after the flip shows up as NaN logits.  Costs one fill of the blob per update. */

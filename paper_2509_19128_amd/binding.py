@@ -22,7 +22,7 @@ EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
     "pl_pack_weights", "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_prefill_async", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
-    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
+    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_set_graphs", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample", "pl_sample_static", "pl_is_ess",
 ]
 
@@ -56,6 +56,7 @@ class Stats(C.Structure):
                 ("kv_pages_free", C.c_int64), ("kv_pages_total", C.c_int64),
                 ("attn_ms", C.c_double), ("gemm_ms", C.c_double), ("sample_ms", C.c_double), ("other_ms", C.c_double),
                 ("attn_launches", C.c_uint64), ("gemm_launches", C.c_uint64), ("attn_kv_bytes", C.c_double),
+                ("attn_shared_ms", C.c_double), ("attn_shared_kv_bytes", C.c_double), ("attn_shared_launches", C.c_uint64),
                 ("prefill_passes", C.c_uint64), ("prefill_positions", C.c_uint64), ("prefill_ms", C.c_double),
                 ("recompute_passes", C.c_uint64), ("recompute_positions", C.c_uint64), ("recompute_ms", C.c_double)]
 
@@ -105,6 +106,7 @@ def lib():
         "pl_debug_kv_pool": (C.c_int, [vp, P(vp), P(i64)]),
         "pl_debug_set_profile": (C.c_int, [vp, i32]),
         "pl_debug_set_poison": (C.c_int, [vp, i32]),
+        "pl_debug_set_graphs": (C.c_int, [vp, i32]),
         "pl_debug_stream_read": (i64, [vp, i64, i32, vp]),
         "pl_attention_workspace_bytes": (i64, [i32, i32, i32, i32, i32]),
         "pl_attention_decode": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
@@ -339,6 +341,9 @@ class Engine:
 
     def debug_set_profile(self, level):
         _check(lib().pl_debug_set_profile(self._h, int(level)))
+
+    def debug_set_graphs(self, on):
+        _check(lib().pl_debug_set_graphs(self._h, int(bool(on))))
 
     def debug_set_poison(self, on):
         _check(lib().pl_debug_set_poison(self._h, int(bool(on))))

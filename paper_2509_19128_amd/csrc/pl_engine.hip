@@ -138,6 +138,18 @@ struct pl_engine {
   int sp_qkv = 1, sp_o = 1, sp_d = 1;
   hipStream_t s_dec = nullptr, s_copy = nullptr;
   hipEvent_t ev_a = nullptr, ev_b = nullptr, ev_c = nullptr;
+  // The kernel sequence of a decode step, captured once per launch shape and replayed: what fixes a
+  // shape is the number of rows, the weight buffer, and the (rounded-up) grid bounds of the two
+  // attention kernels; everything that changes from step to step is read from device buffers.
+  struct StepGraph {
+    int n = 0, buf = 0, items = 0, multi = 0;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    uint64_t last_use = 0;
+  };
+  std::vector<StepGraph> graphs;
+  uint64_t graph_clock = 0;
+  bool use_graphs = true;
   // optional per-kernel-group timing: events[i] closes a segment of category cats[i]
   bool poison_inactive = false;   // debugging aid: after a flip, fill the buffer that went inactive with NaN
   int profile = 0;   // 0 off, 1 events around the attention launches only, 2 around every kernel group
@@ -415,6 +427,56 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
   return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
 }
 
+constexpr size_t MAX_STEP_GRAPHS = 24;
+
+void drop_graph(pl_engine::StepGraph &g) {
+  if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (g.graph) (void)hipGraphDestroy(g.graph);
+  g = pl_engine::StepGraph{};
+}
+
+// Run the decode step's kernels for n rows on the decode stream: as the replay of a captured graph
+// when one may be used (no per-kernel timers), launch by launch otherwise.
+int run_step(pl_engine *e, pl_engine::Work &w, int n) {
+  if (!e->use_graphs || e->profile != 0) return enqueue_step(e, w, n);
+  // grid bounds of the attention kernels in coarse steps, so that few shapes occur; workgroups beyond
+  // the lists' real lengths (which the kernels read from device memory) leave at once
+  w.attn_items = std::min((w.attn_items + 63) / 64 * 64, n * e->attn_max_chunks);
+  if (w.attn_multi) w.attn_multi = std::min((w.attn_multi + 15) / 16 * 16, n);
+  pl_engine::StepGraph *g = nullptr;
+  for (auto &x : e->graphs)
+    if (x.n == n && x.buf == e->active_buf && x.items == w.attn_items && x.multi == w.attn_multi) { g = &x; break; }
+  if (!g) {
+    if (e->graphs.size() >= MAX_STEP_GRAPHS) {   // evict the least recently used
+      size_t lru = 0;
+      for (size_t i = 1; i < e->graphs.size(); ++i)
+        if (e->graphs[i].last_use < e->graphs[lru].last_use) lru = i;
+      drop_graph(e->graphs[lru]);
+      e->graphs.erase(e->graphs.begin() + lru);
+    }
+    pl_engine::StepGraph ng;
+    ng.n = n; ng.buf = e->active_buf; ng.items = w.attn_items; ng.multi = w.attn_multi;
+    HIP_TRY(hipStreamBeginCapture(w.stream, hipStreamCaptureModeThreadLocal));
+    const int rc = enqueue_step(e, w, n);
+    const hipError_t ce = hipStreamEndCapture(w.stream, &ng.graph);
+    if (rc || ce != hipSuccess) {
+      drop_graph(ng);
+      (void)hipGetLastError();
+      return rc ? rc : fail(PL_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
+    }
+    const hipError_t ie = hipGraphInstantiate(&ng.exec, ng.graph, nullptr, nullptr, 0);
+    if (ie != hipSuccess) {
+      drop_graph(ng);
+      return fail(PL_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(ie));
+    }
+    e->graphs.push_back(ng);
+    g = &e->graphs.back();
+  }
+  g->last_use = ++e->graph_clock;
+  HIP_TRY(hipGraphLaunch(g->exec, w.stream));
+  return PL_OK;
+}
+
 void activate_staged(pl_engine *e) {
   if (e->cfg.n_weight_buffers == 2) e->active_buf ^= 1;
   e->version = e->staged_version;
@@ -638,6 +700,7 @@ void pl_destroy(pl_engine *e) {
     void *hst[] = {e->pt_h, e->wk[0].meta_h, e->tok_h, e->lp_h};
     for (void *p : hst)
       if (p) (void)hipHostFree(p);
+    for (auto &g : e->graphs) drop_graph(g);
     hipStream_t s_pre = e->wk[1].stream;
     free_work(e->wk[0]);
     free_work(e->wk[1]);
@@ -867,6 +930,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     }
   }
   if (!e->dry && !n_reading && e->pre_pending && hipEventQuery(e->ev_pre_last) == hipSuccess) e->pre_pending = false;
+  const bool shared_gpu = e->pre_pending;   // a cache-only pass may run beside this step's kernels
   int n = 0;
   int64_t new_pages = 0;
   for (int s = 0; s < c.max_batch; ++s) {
@@ -975,7 +1039,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     }
     HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
     HIP_TRY(hipEventRecord(e->ev_a, s));
-    int rc = enqueue_step(e, w, n);
+    int rc = run_step(e, w, n);
     if (rc) return rc;
     HIP_TRY(hipEventRecord(e->ev_b, s));
     HIP_TRY(hipMemcpyAsync(e->tok_h, e->tok_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
@@ -986,7 +1050,10 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, e->prof_ev[i - 1], e->prof_ev[i]) != hipSuccess) continue;
       switch (e->prof_cat[i]) {
-        case CAT_ATTN: e->st.attn_ms += ms; e->st.attn_launches++; e->st.attn_kv_bytes += (kv_tokens + n) * 4.0 * c.n_kv_heads * c.head_dim; break;
+        case CAT_ATTN:
+          e->st.attn_ms += ms; e->st.attn_launches++; e->st.attn_kv_bytes += (kv_tokens + n) * 4.0 * c.n_kv_heads * c.head_dim;
+          if (shared_gpu) { e->st.attn_shared_ms += ms; e->st.attn_shared_launches++; e->st.attn_shared_kv_bytes += (kv_tokens + n) * 4.0 * c.n_kv_heads * c.head_dim; }
+          break;
         case CAT_GEMM: e->st.gemm_ms += ms; break;
         case CAT_SAMPLE: e->st.sample_ms += ms; break;
         default: e->st.other_ms += ms;
@@ -1145,6 +1212,12 @@ int pl_debug_write_kv(pl_engine *e, int32_t slot, int32_t layer, const float *k_
 int pl_debug_set_profile(pl_engine *e, int32_t level) {
   if (!e || level < 0 || level > 2) return fail(PL_E_INVAL, "bad argument");
   e->profile = e->dry ? 0 : level;
+  return PL_OK;
+}
+
+int pl_debug_set_graphs(pl_engine *e, int32_t on) {
+  if (!e) return fail(PL_E_INVAL, "NULL argument");
+  e->use_graphs = on != 0;
   return PL_OK;
 }
 

@@ -650,3 +650,49 @@ def test_background_prompt_reading_across_an_update_and_a_retire(weights):
         out = eng.decode_step()
         assert np.isfinite(eng.debug_get_logits(out["n"])).all()
     eng.close(); ref.close()
+
+
+# ---- the step replayed from a captured graph ---------------------------------------------------------
+
+def test_steps_replayed_from_a_graph_equal_steps_launched_kernel_by_kernel(weights):
+    """Every replay against the eager result, bit for bit, over a run in which the launch shape keeps
+    changing (sequences finish and are refilled, so the row count varies; contexts cross the attention
+    chunk; updates flip the weight buffer) and eager work of the program's own (blocking and background
+    prompt reading, staging copies, synchronisations) runs between the replays."""
+    master, pert = weights
+    rng_p = np.random.default_rng(61)
+    lens = [3, 9, 17, 30]
+    prompts = [rng_p.integers(0, M.vocab, n).astype(np.int32) for n in (5, 40, 12, 70, 33, 8, 21)]
+    runs = []
+    for graphs in (False, True):
+        eng = _engine(max_batch=4, max_context=256, kv_pool_tokens=4 * 256)
+        eng.debug_set_graphs(graphs)
+        blobs = [eng.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
+        eng.load_weights(blobs[0])
+        nxt = 0
+        for i in range(4):
+            eng.add_sequence(i, prompts[nxt], lens[i]); nxt += 1
+        rec = []
+        for step in range(70):
+            if step in (11, 25, 48):
+                eng.swap_weights(blobs[(step % 2)], flags=pl.PL_SWAP_WAIT)
+            out = eng.decode_step()
+            rec.append((out["slot"].copy(), out["token"].copy(), out["logprob"].copy(), out["weight_version"].copy(),
+                        eng.debug_get_logits(out["n"])))
+            for s, f in zip(out["slot"].tolist(), out["finished"].tolist()):
+                if f:
+                    eng.retire_sequence(s)
+                    if nxt < len(prompts):
+                        slot = eng.add_sequence(100 + nxt, prompts[nxt], 25)
+                        if nxt % 2:
+                            eng.prefill(slot)          # blocking passes between two replays
+                        nxt += 1
+        runs.append(rec)
+        eng.close()
+    assert len(runs[0]) == len(runs[1])
+    shapes = set()
+    for a, b in zip(*runs):
+        shapes.add(len(a[0]))
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    assert len(shapes) >= 3       # the run did go through several launch shapes
