@@ -252,6 +252,17 @@ int pl_debug_set_poison(pl_engine *e, int32_t on);
 /* Device pointer and size of the KV page pool (to fill it with synthetic values). */
 int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 
+/* One launch of one tile configuration of the GEMM kernel over output columns [n_begin, n_end) (tuning
+ * and tests).  cfg: 0 32x256, 1 64x256, 2 128x256, 3 64x128, 4 128x128, 5 256x128, 6 64x64, 7 128x64,
+ * 8 32x128 (rows x columns of a workgroup's tile; 6-8 mode 0 only), 9 128x64 and 10 256x64 with the
+ * wavefronts stacked along the rows.  mode and splits as in pl_gemm_bf16, except that mode 1 accepts
+ * splits > 1: the partial sums then go to ws (device fp32 [splits, M, n_end - n_begin]) and a second
+ * kernel applies the SwiGLU to their sum.  paired != 0 (splits = 1 only) lays the grid out so that the
+ * row tiles of one column tile run on the same XCD at the same time.  PL_E_INVAL (nothing launched)
+ * for shapes the configuration does not cover. */
+int pl_debug_gemm_cfg(int32_t cfg, const void *x, const void *w, void *y, void *ws, int32_t M, int32_t N, int32_t K,
+                      int32_t mode, int32_t splits, int32_t n_begin, int32_t n_end, int32_t paired, void *stream);
+
 /* Launch a kernel that only reads the device buffer (contiguous 16-byte loads, 8 in flight per lane;
  * ordinary loads, or non-temporal ones if `nontemporal` is non-zero) on `stream`; returns the number of bytes it reads (a multiple of 256 MiB, <= nbytes) or a negative
  * pl_status.  Timed by the caller, it gives the read bandwidth HBM delivers on this board. */

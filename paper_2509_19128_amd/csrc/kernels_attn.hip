@@ -255,49 +255,66 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
   if (b == 0) { work[0] = total_full + n_last; work[1] = n_multi; }
 }
 
-// Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup per (listed sequence,
-// kv head); the list is the work-list kernel's, the grid is sized by the caller's bound on its length.
+// Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup of HD threads per
+// (listed sequence, query head); the list is the work-list kernel's, the grid is sized by the
+// caller's bound on its length.  The kernel is latency bound (a few KiB per workgroup), so every load
+// that does not depend on another is issued at once: thread c fetches the statistics of chunk c, the
+// weights go through LDS, and each thread then sums its output element over the chunks, eight loads
+// at a time, in chunk order.
 template <int HD>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
+__global__ __launch_bounds__(HD < 64 ? 64 : HD) void attn_combine_kernel(AttnParams p) {
+  constexpr int NT = HD < 64 ? 64 : HD;   // threads: whole wavefronts; thread d < HD owns output element d
   if ((int)blockIdx.y >= p.work[1]) return;
-  const int b = p.multi[blockIdx.y], g = blockIdx.x;
+  const int b = p.multi[blockIdx.y], hq = blockIdx.x;
+  const int G = p.Hq / p.Hkv, g = hq / G, h = hq % G;
   const int ctx = p.ctx_len[b];
-  const int G = p.Hq / p.Hkv;
   const int nchunk = (ctx + p.chunk - 1) / p.chunk;
   const int64_t base = ((int64_t)b * p.Hkv + g) * p.max_chunks;
-  for (int idx = threadIdx.x; idx < G * HD; idx += 256) {
-    const int h = idx / HD, d = idx % HD;
-    const float *ml = p.part_ml + (base * G + h) * 2;     // chunk c at ml[c * G * 2]
-    const float *po = p.part_o + (base * G + h) * HD + d; // chunk c at po[c * G * HD]
-    // loads of up to 8 chunks are issued together; the sums stay in chunk order
-    float M = -INFINITY;
-    for (int c0 = 0; c0 < nchunk; c0 += 8) {
-      float m8[8];
+  const float *ml = p.part_ml + (base * G + h) * 2;                   // chunk c at ml[c * G * 2]
+  const float *po = p.part_o + (base * G + h) * HD + (threadIdx.x < HD ? threadIdx.x : 0);   // chunk c at po[c * G * HD]
+  __shared__ float sw[NT];      // weight of chunk c (NT chunks at a time)
+  __shared__ float red[2][NT / 64];
+  const int d = threadIdx.x, lane = d & 63, wave = d >> 6;
+  float O = 0.f, L = 0.f;
+  // the running maximum over all chunks first (chunks beyond HD are walked in rounds of HD)
+  float M = -INFINITY;
+  for (int c0 = 0; c0 < nchunk; c0 += NT) {
+    float m = c0 + d < nchunk ? ml[(int64_t)(c0 + d) * G * 2] : -INFINITY;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) m8[u] = c0 + u < nchunk ? ml[(int64_t)(c0 + u) * G * 2] : -INFINITY;
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    if (lane == 0) red[0][wave] = m;
+    __syncthreads();
 #pragma unroll
-      for (int u = 0; u < 8; ++u) M = fmaxf(M, m8[u]);
-    }
-    float L = 0.f, O = 0.f;
-    for (int c0 = 0; c0 < nchunk; c0 += 8) {
-      float m8[8], l8[8], o8[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (c0 + u < nchunk) {
-          m8[u] = ml[(int64_t)(c0 + u) * G * 2];
-          l8[u] = ml[(int64_t)(c0 + u) * G * 2 + 1];
-          o8[u] = po[(int64_t)(c0 + u) * G * HD];
-        }
-#pragma unroll
-      for (int u = 0; u < 8; ++u)
-        if (c0 + u < nchunk) {
-          const float f = __builtin_amdgcn_exp2f(m8[u] - M);
-          L += l8[u] * f;
-          O += o8[u] * f;
-        }
-    }
-    p.out[((int64_t)b * p.Hq + g * G + h) * HD + d] = (__bf16)(O / L);
+    for (int w = 0; w < NT / 64; ++w) M = fmaxf(M, red[0][w]);
+    __syncthreads();
   }
+  for (int c0 = 0; c0 < nchunk; c0 += NT) {
+    const int nc = min(NT, nchunk - c0);
+    float wgt = 0.f, lw = 0.f;
+    if (d < nc) {
+      const float2 v = *(const float2 *)(ml + (int64_t)(c0 + d) * G * 2);
+      wgt = __builtin_amdgcn_exp2f(v.x - M);
+      lw = v.y * wgt;
+    }
+    sw[d] = wgt;
+    // L: sum of l_c w_c in a fixed order (lanes by shuffle tree, then the waves in order)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o, 64);
+    if (lane == 0) red[1][wave] = lw;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) L += red[1][w];
+    for (int c = 0; c < nc; c += 8) {
+      float o8[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) o8[u] = c + u < nc ? po[(int64_t)(c0 + c + u) * G * HD] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (c + u < nc) O += o8[u] * sw[c + u];
+    }
+    __syncthreads();
+  }
+  if (d < HD) p.out[((int64_t)b * p.Hq + hq) * HD + d] = (__bf16)(O / L);
 }
 
 }  // namespace
@@ -330,20 +347,20 @@ int launch_attention(const AttnParams &p, hipStream_t s) {
   if (p.n_seq <= 0) return 0;
   // max_items and max_multi bound the two lists (a host that knows the step's contexts passes the
   // exact lengths; otherwise n_seq * max_chunks and n_seq)
-  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hkv, p.max_multi > 0 ? p.max_multi : 1);
+  dim3 grid(p.max_items * p.Hkv), cgrid(p.Hq, p.max_multi > 0 ? p.max_multi : 1);
   const bool merge = p.max_multi > 0;
   switch (p.hd) {
     case 128:
       hipLaunchKernelGGL((attn_decode_kernel<128, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      if (merge) hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(256), 0, s, p);
+      if (merge) hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(128), 0, s, p);
       break;
     case 64:
       hipLaunchKernelGGL((attn_decode_kernel<64, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      if (merge) hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(256), 0, s, p);
+      if (merge) hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p);
       break;
     case 32:
       hipLaunchKernelGGL((attn_decode_kernel<32, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
-      if (merge) hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(256), 0, s, p);
+      if (merge) hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(64), 0, s, p);
       break;
     default:
       return -1;

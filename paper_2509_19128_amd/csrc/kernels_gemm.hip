@@ -9,6 +9,7 @@
 // fixed order) so that narrow outputs still occupy every compute unit.
 #include "pl_common.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace pl {
@@ -26,7 +27,7 @@ constexpr int LDS_ROW = 72;     // padded row length (elements) of the x tile in
 template <int WM, int WN, int AT, int BT, int MODE>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
                                                    void *__restrict__ Yv, int M, int N, int K, int ksteps,
-                                                   int n_base, int n_end, int nrow) {
+                                                   int n_base, int n_end, int nrow, int ldy, int y_col0) {
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
   constexpr int XCH = BM * (BK / 8) / 256;       // 16-byte chunks of the x tile per thread
   static_assert(WM * WN == 4 && XCH >= 1, "tile");
@@ -193,17 +194,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
       const int m = m0 + wm * AT * 32 + a * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
       if (m >= M) continue;
       if (MODE == 0) {
-        float *Y = (float *)Yv + ((int64_t)split * M + m) * N;
+        // partial sums of slice `split`: row stride ldy, columns counted from y_col0
+        float *Y = (float *)Yv + ((int64_t)split * M + m) * ldy - y_col0;
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
           int n = n0 + b * 32 + lrow;
-          if (n < N) Y[n] = acc[a][b][i];
+          if (n < n_end) Y[n] = acc[a][b][i];
         }
       } else {
         // SwiGLU: the two column tiles of a wavefront are the gate and the up half of a 64-row block
         bf16_t *Y = (bf16_t *)Yv + (int64_t)m * (N / 2);
         int n = n0 + lrow;
-        if (n < N) {
+        if (n < n_end) {
           float gte = acc[a][0][i], up = acc[a][BT - 1][i];
           float sv = gte / (1.f + __expf(-gte));
           Y[(n0 >> 1) + lrow] = (__bf16)(sv * up);
@@ -213,76 +215,189 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
   }
 }
 
+// SwiGLU over K-split partial sums: parts [splits][M][ld] holds columns [col0, col0 + ld) of the
+// interleaved gate/up product (blocks of 64 columns: 32 gate, then the 32 matching up columns);
+// mid[m][(col0 + c) / 2 ...] = silu(sum_s gate) * (sum_s up), slices added in order.
+__global__ __launch_bounds__(256) void swiglu_reduce_kernel(const float *__restrict__ parts, int splits, int M, int ld,
+                                                            int col0, bf16_t *__restrict__ mid, int F) {
+  const int half_ld = ld >> 1;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)M * half_ld) return;
+  const int m = (int)(idx / half_ld), j = (int)(idx % half_ld);
+  const int c = (j >> 5) * 64 + (j & 31);
+  float g = 0.f, u = 0.f;
+  for (int sl = 0; sl < splits; ++sl) {
+    const float *row = parts + ((int64_t)sl * M + m) * ld;
+    g += row[c];
+    u += row[c + 32];
+  }
+  const float sv = g / (1.f + __expf(-g));
+  mid[(int64_t)m * F + (col0 >> 1) + j] = (__bf16)(sv * u);
+}
+
+struct Launch {
+  const bf16_t *x, *w;
+  void *y;
+  int M, N, K, mode, splits, n_begin, n_end, ldy, y_col0;
+  bool paired;
+  hipStream_t s;
+};
+
 // Launch over output columns [n_begin, n_end) (multiples of the tile width, except the matrix edge).
 template <int WM, int WN, int AT, int BT>
-int launch_cfg(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,
-               int n_begin, int n_end, hipStream_t s, bool paired = false) {
+int launch_cfg(const Launch &L) {
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
-  if (n_end <= n_begin) return 0;
-  dim3 grid((n_end - n_begin + BN - 1) / BN, splits, (M + BM - 1) / BM);
+  if (L.n_end <= L.n_begin) return 0;
+  if (BT == 1 && L.mode == 1) return -1;   // the SwiGLU epilogue needs a gate and an up tile per wavefront
+  dim3 grid((L.n_end - L.n_begin + BN - 1) / BN, L.splits, (L.M + BM - 1) / BM);
   int nrow = 0;
-  if (paired) {   // flat grid, column tiles padded to a multiple of 8 (see the kernel)
+  if (L.paired) {   // flat grid, column tiles padded to a multiple of 8 (see the kernel)
     nrow = grid.z;
     grid.x = ((grid.x + 7) / 8) * 8 * nrow;
     grid.z = 1;
   }
-  int ksteps = 4 * ((K / (4 * BK) + splits - 1) / splits);
-  if (mode == 0)
-    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 0>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin,
-                       n_end, nrow);
+  int ksteps = 4 * ((L.K / (4 * BK) + L.splits - 1) / L.splits);
+  if (L.mode == 0)
+    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 0>), grid, dim3(256), 0, L.s, L.x, L.w, L.y, L.M, L.N, L.K, ksteps,
+                       L.n_begin, L.n_end, nrow, L.ldy, L.y_col0);
   else
-    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, BT, 1>), grid, dim3(256), 0, s, x, w, y, M, N, K, ksteps, n_begin,
-                       n_end, nrow);
+    hipLaunchKernelGGL((gemm_kernel<WM, WN, AT, (BT > 1 ? BT : 2), 1>), grid, dim3(256), 0, L.s, L.x, L.w, L.y, L.M, L.N,
+                       L.K, ksteps, L.n_begin, L.n_end, nrow, L.ldy, L.y_col0);
+  return hipGetLastError() == hipSuccess ? 0 : -7;
+}
+
+int launch_by_id(int cfg, const Launch &L) {
+  switch (cfg) {
+    case GEMM_32x256: return launch_cfg<1, 4, 1, 2>(L);
+    case GEMM_64x256: return launch_cfg<1, 4, 2, 2>(L);
+    case GEMM_128x256: return launch_cfg<1, 4, 4, 2>(L);
+    case GEMM_64x128: return launch_cfg<2, 2, 1, 2>(L);
+    case GEMM_128x128: return launch_cfg<2, 2, 2, 2>(L);
+    case GEMM_256x128: return launch_cfg<2, 2, 4, 2>(L);
+    case GEMM_64x64: return launch_cfg<2, 2, 1, 1>(L);
+    case GEMM_128x64: return launch_cfg<2, 2, 2, 1>(L);
+    case GEMM_32x128: return launch_cfg<1, 4, 1, 1>(L);
+    case GEMM_128x64P: return launch_cfg<4, 1, 1, 2>(L);
+    case GEMM_256x64P: return launch_cfg<4, 1, 2, 2>(L);
+    default: return -1;
+  }
+}
+
+bool splits_valid(int K, int splits) {
+  const int total = K / (4 * BK);
+  return splits >= 1 && splits <= total && (splits - 1) * ((total + splits - 1) / splits) < total;   // no empty slice
+}
+
+int swiglu_reduce(const float *parts, int splits, int M, int ld, int col0, bf16_t *mid, int F, hipStream_t s) {
+  const int64_t total = (int64_t)M * (ld / 2);
+  hipLaunchKernelGGL(swiglu_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, parts, splits, M, ld, col0, mid, F);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
 }  // namespace
 
-int gemm_pick_splits(int M, int N, int K) {
-  // One workgroup fits on a compute unit: split K so that the output tiles times the number of
-  // slices comes close to, but not above, the 256 units, with at least 4 k-steps per slice.
-  int total = K / (4 * BK), best = 1;   // slices are made of groups of 4 k-steps
-  // Short K at 129..256 rows: 128 x 128 tiles, two workgroups per unit, four slices (measured best
-  // for the QKV and O projections of the 7B shape: fewer partial sums to write and to add up).
-  if (M > 128 && M <= 256 && K <= 4096 && total >= 4 && 3 * ((total + 3) / 4) < total) return 4;
-  int bn = M > 128 ? 128 : 256;
-  int tiles = ((N + bn - 1) / bn) * ((M + 255) / 256);
-  for (int s = 2; s <= 32 && tiles * s <= 256; ++s) {
-    int c = (total + s - 1) / s;
-    if ((s - 1) * c >= total) continue;   // slices must be non-empty
-    best = s;
-  }
-  return best;
+int gemm_tile_rows(int cfg) {
+  static const int rows[GEMM_N_CFGS] = {32, 64, 128, 64, 128, 256, 64, 128, 32, 128, 256};
+  return cfg >= 0 && cfg < GEMM_N_CFGS ? rows[cfg] : 0;
 }
 
-int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,
-                hipStream_t s) {
-  if (M < 1 || M > 512 || K % (4 * BK) || N % 32 || splits < 1 || splits > K / (4 * BK)) return -1;
-  if ((splits - 1) * ((K / (4 * BK) + splits - 1) / splits) >= K / (4 * BK)) return -1;   // an empty slice
-  if (mode == 1 && (splits != 1 || N % 64)) return -1;
+// One launch of one tile configuration over a column range (tuning and tests).  mode 1 with
+// splits > 1 writes fp32 partials to ws and finishes with the SwiGLU reduction.
+int launch_gemm_cfg(int cfg, const bf16_t *x, const bf16_t *w, void *y, float *ws, int M, int N, int K, int mode,
+                    int splits, int n_begin, int n_end, bool paired, hipStream_t s) {
+  if (M < 1 || M > 512 || K % (4 * BK) || N % 32 || !splits_valid(K, splits)) return -1;
   if (mode != 0 && mode != 1) return -1;
-  // beyond this the descriptor's size field and the 32-bit offsets wrap and loads read zeros
+  if (mode == 1 && (N % 64 || n_begin % 64 || n_end % 64)) return -1;
+  if (n_begin < 0 || n_end > N || n_begin % 32 || n_end % 32) return -1;
   if ((int64_t)N * K * 2 >= GEMM_MAX_OPERAND_BYTES || (int64_t)M * K * 2 >= GEMM_MAX_OPERAND_BYTES) return -1;
-  if (M <= 32) return launch_cfg<1, 4, 1, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
-  if (M <= 64) return launch_cfg<1, 4, 2, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
-  if (M <= 128) return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
-  if (M <= 256 && splits == 1 && N >= 128 * 256) {
-    // Wide matrices without a K split: 128 x 256 tiles in XCD-local pairs.  Each wavefront owns its
-    // own 64 columns of W (no fragment is loaded twice by one workgroup) and the x tile is half as
-    // tall, which cuts the vector-memory and LDS-store traffic per MFMA; the second row tile reads W
-    // from L2.  When the tile count is a little over a multiple of 256 the last round would run on a
-    // few units at full length: those columns go to a second launch of 64 x 128 tiles instead.
-    const int ctiles = (N + 255) / 256, tiles = 2 * ctiles, rem = tiles % 256;
-    if (tiles > 256 && rem > 0 && rem <= 64) {
-      const int n_main = ((tiles - rem) / 2) * 256;
-      int rc = launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, n_main, s, true);
-      return rc ? rc : launch_cfg<2, 2, 1, 2>(x, w, y, M, N, K, mode, splits, n_main, N, s);
-    }
-    return launch_cfg<1, 4, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s, true);
+  if (paired && splits != 1) return -1;
+  Launch L{x, w, y, M, N, K, mode, splits, n_begin, n_end, N, 0, paired, s};
+  if (mode == 1 && splits > 1) {
+    if (!ws) return -1;
+    L.mode = 0; L.y = ws; L.ldy = n_end - n_begin; L.y_col0 = n_begin;
+    int rc = launch_by_id(cfg, L);
+    return rc ? rc : swiglu_reduce(ws, splits, M, n_end - n_begin, n_begin, (bf16_t *)y, N / 2, s);
   }
-  if (M <= 256 && splits > 1 && K <= 4096) return launch_cfg<2, 2, 2, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
-  // otherwise 256 x 128 tiles, one per compute unit and round
-  return launch_cfg<2, 2, 4, 2>(x, w, y, M, N, K, mode, splits, 0, N, s);
+  return launch_by_id(cfg, L);
+}
+
+// K split of a mode-0 product for calls of up to M rows.  The tile shapes named here are the ones
+// launch_gemm uses for such calls; the counts come from sweeps over tile shape and split count at the
+// benchmark's shapes (weights cold, launches back to back): a launch costs a fixed 3-9 us (first
+// loads, drain, partial sums written) plus its weight bytes at 3.5-4.5 TB/s, so narrow outputs want
+// about one workgroup per compute unit and as few slices as that allows.
+int gemm_pick_splits(int M, int N, int K) {
+  auto largest = [&](int tiles, int cap) {
+    int best = 1;
+    for (int sp = 2; sp <= 32 && tiles * sp <= cap; ++sp)
+      if (splits_valid(K, sp)) best = sp;
+    return best;
+  };
+  if (M <= 64 && N < 16384) return largest((N + 63) / 64, 256);                 // 64 x 64 tiles
+  if (M <= 128) return largest((N + 255) / 256, 256);                           // 128 x 256 tiles
+  if (M <= 256 && K <= 4096) return splits_valid(K, 2) ? 2 : 1;                  // 128 x 64 tiles, two slices
+  if (M <= 256) return largest(((N + 255) / 256) * 2, 232);                     // 128 x 256 tiles
+  return largest(((N + 127) / 128) * ((M + 255) / 256), 256);                   // 256 x 128 tiles
+}
+
+// How K is split for a product, as a function of the LARGEST row count the caller will ever pass
+// (so that every pass, whatever its row count, adds up each output element in the same order).
+// mode 0: one split count for all columns (the caller's output holds that many slices).
+// mode 1: columns [0, n_main) with `splits` slices, columns [n_main, N) with `rem_splits`; wherever a
+// count exceeds 1 the partial sums go through the workspace and the SwiGLU is applied by a reduction.
+// In the sweeps no SwiGLU product gained from a K split (64 x 128 tiles fill the chip for narrow
+// batches, and the column remainder of the wide ones is bound by its fixed costs), so none is chosen.
+GemmSplit gemm_pick_split(int M_max, int N, int K, int mode) {
+  GemmSplit ks{1, N, 1};
+  if (mode == 0) ks.splits = gemm_pick_splits(M_max, N, K);
+  return ks;
+}
+
+// fp32 elements of workspace a mode-1 product of up to M_max rows needs (0 if K is not split)
+int64_t gemm_workspace_elems(int M_max, int N, const GemmSplit &ks) {
+  int64_t need = 0;
+  if (ks.splits > 1) need = (int64_t)ks.splits * M_max * ks.n_main;
+  if (ks.n_main < N && ks.rem_splits > 1) need = std::max<int64_t>(need, (int64_t)ks.rem_splits * M_max * (N - ks.n_main));
+  return need;
+}
+
+int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, float *ws, int M, int N, int K, int mode,
+                const GemmSplit &ks, hipStream_t s) {
+  if (M < 1 || M > 512 || K % (4 * BK) || N % 32 || !splits_valid(K, ks.splits)) return -1;
+  if (mode != 0 && mode != 1) return -1;
+  if (mode == 1 && (N % 64 || ks.n_main % 64 || !splits_valid(K, ks.rem_splits))) return -1;
+  if (mode == 0 && ks.n_main != N) return -1;
+  if (ks.n_main < 0 || ks.n_main > N) return -1;
+  // tile shape from the rows of this call
+  int cfg;
+  bool paired = false;
+  if (mode == 1) {
+    if (M <= 32) cfg = GEMM_32x256;
+    else if (M <= 64) cfg = GEMM_64x128;
+    else if (M <= 128) cfg = GEMM_128x256;
+    else if (M <= 256 && N >= 128 * 256) { cfg = GEMM_128x256; paired = ks.splits == 1; }
+    else cfg = GEMM_256x128;
+  } else {
+    if (M <= 32) cfg = N >= 8192 ? GEMM_32x256 : GEMM_32x128;
+    else if (M <= 64) cfg = N >= 16384 ? GEMM_64x256 : GEMM_64x64;
+    else if (M <= 128) cfg = GEMM_128x256;
+    else if (M <= 256 && ks.splits == 1 && N >= 128 * 256) { cfg = GEMM_128x256; paired = true; }
+    else if (M <= 256 && K <= 4096) cfg = GEMM_128x64;
+    else if (M <= 256) cfg = GEMM_128x256;
+    else cfg = GEMM_256x128;
+  }
+  int n_main = ks.n_main;
+  if (paired && n_main == N) {
+    // Wide matrices without a K split: 128 x 256 tiles in XCD-local pairs.  When the tile count is a
+    // little over a multiple of 256 the last round would run on a few units at full length: those
+    // columns go to a second launch of 64 x 128 tiles instead.
+    const int ctiles = (N + 255) / 256, tiles = 2 * ctiles, rem = tiles % 256;
+    if (tiles > 256 && rem > 0 && rem <= 64) n_main = ((tiles - rem) / 2) * 256;
+  }
+  int rc = launch_gemm_cfg(cfg, x, w, y, ws, M, N, K, mode, ks.splits, 0, n_main, paired, s);
+  if (rc || n_main == N) return rc;
+  return launch_gemm_cfg(GEMM_64x128, x, w, y, ws, M, N, K, mode, mode == 1 ? ks.rem_splits : ks.splits, n_main, N,
+                         false, s);
 }
 
 }  // namespace pl

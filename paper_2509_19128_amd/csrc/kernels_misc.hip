@@ -114,13 +114,16 @@ __global__ void rope_tables_kernel(const int32_t *pos, float *cs, int32_t *ctx_l
 }
 
 // qkv (fp32, split-K partials) -> rotated q (bf16), rotated k and v into the row's cache page.
-// One block per (row, head of q|k|v), one thread per rotated pair.
-__global__ void rope_append_kernel(const float *qkv, int splits, const float *cs, const int32_t *pos,
-                                   const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out,
-                                   bf16_t *kv_layer, int n, int Hq, int Hkv, int hd, int page_tokens,
-                                   int pages_per_seq) {
-  const int row = blockIdx.y, hh = blockIdx.x, i = threadIdx.x;
+// One thread per rotated pair (or pair of value elements); a workgroup of 256 threads covers 256
+// consecutive pairs of one row, i.e. several heads of q|k|v.
+__global__ __launch_bounds__(256) void rope_append_kernel(const float *qkv, int splits, const float *cs, const int32_t *pos,
+                                                          const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out,
+                                                          bf16_t *kv_layer, int n, int Hq, int Hkv, int hd, int page_tokens,
+                                                          int pages_per_seq) {
   const int half = hd / 2;
+  const int pair = blockIdx.x * 256 + threadIdx.x;
+  if (pair >= (Hq + 2 * Hkv) * half) return;
+  const int row = blockIdx.y, hh = pair / half, i = pair % half;
   const int width = (Hq + 2 * Hkv) * hd;
   float x1 = 0.f, x2 = 0.f;
   // loads of up to 8 slices are issued together, the adds stay in slice order
@@ -221,7 +224,7 @@ int launch_rope_append(const float *qkv, int splits, const float *cs, const int3
                        const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out, bf16_t *kv_layer,
                        int n, int Hq, int Hkv, int hd, int page_tokens, int pages_per_seq, hipStream_t s) {
   if (n <= 0) return 0;
-  hipLaunchKernelGGL(rope_append_kernel, dim3(Hq + 2 * Hkv, n), dim3(hd / 2), 0, s, qkv, splits, cs, pos, row_slot,
+  hipLaunchKernelGGL(rope_append_kernel, dim3(((Hq + 2 * Hkv) * (hd / 2) + 255) / 256, n), dim3(256), 0, s, qkv, splits, cs, pos, row_slot,
                      page_table, q_out, kv_layer, n, Hq, Hkv, hd, page_tokens, pages_per_seq);
   return ok();
 }

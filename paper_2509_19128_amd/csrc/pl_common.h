@@ -49,8 +49,22 @@ int attention_chunk_tokens(int n_seq, int Hkv, int max_ctx);
 // x and W are each addressed through one buffer descriptor with 32-bit byte offsets kept in signed
 // registers: an operand must stay below 2 GiB (launch_gemm returns -1 beyond that).
 constexpr int64_t GEMM_MAX_OPERAND_BYTES = (int64_t)1 << 31;
-int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, int M, int N, int K, int mode, int splits,
-                hipStream_t s);
+// tile configurations of the GEMM kernel: rows x columns of a workgroup's tile ("P": the four wavefronts
+// stacked along the rows, each holding a gate and an up tile)
+enum { GEMM_32x256, GEMM_64x256, GEMM_128x256, GEMM_64x128, GEMM_128x128, GEMM_256x128, GEMM_64x64, GEMM_128x64,
+       GEMM_32x128, GEMM_128x64P, GEMM_256x64P, GEMM_N_CFGS };
+// How K is split: columns [0, n_main) in `splits` slices, columns [n_main, N) in `rem_splits` (mode 1
+// only; mode 0 has n_main = N).  Chosen once per product from the largest row count (gemm_pick_split),
+// so that every call adds up an output element in the same order whatever its row count.
+struct GemmSplit { int splits, n_main, rem_splits; };
+GemmSplit gemm_pick_split(int M_max, int N, int K, int mode);
+int64_t gemm_workspace_elems(int M_max, int N, const GemmSplit &ks);
+// ws: fp32 workspace of gemm_workspace_elems (mode 1 with split K), else may be null
+int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, float *ws, int M, int N, int K, int mode,
+                const GemmSplit &ks, hipStream_t s);
+int launch_gemm_cfg(int cfg, const bf16_t *x, const bf16_t *w, void *y, float *ws, int M, int N, int K, int mode,
+                    int splits, int n_begin, int n_end, bool paired, hipStream_t s);
+int gemm_tile_rows(int cfg);
 int gemm_pick_splits(int M, int N, int K);
 
 struct SampleParams {

@@ -135,7 +135,7 @@ struct pl_engine {
   int32_t *tok_h = nullptr;
   float *lp_h = nullptr;
   int attn_chunk = 1024, attn_max_chunks = 1;
-  int sp_qkv = 1, sp_o = 1, sp_d = 1;
+  pl::GemmSplit ks_qkv{1, 0, 1}, ks_o{1, 0, 1}, ks_gu{1, 0, 1}, ks_d{1, 0, 1}, ks_lm{1, 0, 1};
   hipStream_t s_dec = nullptr, s_copy = nullptr;
   hipEvent_t ev_a = nullptr, ev_b = nullptr, ev_c = nullptr;
   // The kernel sequence of a decode step, captured once per launch shape and replayed: what fixes a
@@ -289,11 +289,15 @@ int alloc_device(pl_engine *e) {
   const int B = c.max_batch;
   const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
   const int64_t wq = qd + 2 * kvd;
-  e->sp_qkv = pl::gemm_pick_splits(B, (int)wq, (int)d);
-  e->sp_o = pl::gemm_pick_splits(B, (int)d, (int)qd);
-  e->sp_d = pl::gemm_pick_splits(B, (int)d, c.d_ffn);
+  // K splits are fixed by max_batch alone: a pass of any row count adds up every element in the same order
+  e->ks_qkv = pl::gemm_pick_split(B, (int)wq, (int)d, 0);
+  e->ks_o = pl::gemm_pick_split(B, (int)d, (int)qd, 0);
+  e->ks_gu = pl::gemm_pick_split(B, 2 * c.d_ffn, (int)d, 1);
+  e->ks_d = pl::gemm_pick_split(B, (int)d, c.d_ffn, 0);
+  e->ks_lm = pl::GemmSplit{1, c.vocab, 1};
   const int64_t R = e->rows_cap;   // rows of the activation buffers (cache-only passes take up to 256 rows)
-  const int64_t parts = std::max(std::max(e->sp_qkv * wq, e->sp_o * d), e->sp_d * d) * R;
+  const int64_t parts = std::max(std::max(std::max(e->ks_qkv.splits * wq, e->ks_o.splits * d), e->ks_d.splits * d) * R,
+                                 pl::gemm_workspace_elems((int)R, 2 * c.d_ffn, e->ks_gu));
   // the chunk length is fixed by max_batch alone, so a sequence's attention result never depends on
   // how many rows a pass holds
   e->attn_chunk = pl::attention_chunk_tokens(B, c.n_kv_heads, c.max_context);
@@ -386,9 +390,9 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
     const LayerW lw = layer_weights(e, l);
     bf16_t *kv_layer = e->kv_pool + (int64_t)l * e->layer_stride;
     if (timed) mark(e, CAT_OTHER);
-    rc |= pl::launch_gemm(w.a, lw.w_qkv, w.parts, n, wq, d, 0, e->sp_qkv, s);
+    rc |= pl::launch_gemm(w.a, lw.w_qkv, w.parts, nullptr, n, wq, d, 0, e->ks_qkv, s);
     if (timed) mark(e, CAT_GEMM);
-    rc |= pl::launch_rope_append(w.parts, e->sp_qkv, w.cs, w.m_pos(true), w.m_row_slot(true), e->pt_d,
+    rc |= pl::launch_rope_append(w.parts, e->ks_qkv.splits, w.cs, w.m_pos(true), w.m_row_slot(true), e->pt_d,
                                  w.q_rot, kv_layer, n, c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens,
                                  e->pages_per_seq, s);
     pl::AttnParams ap{};
@@ -403,19 +407,19 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
     if (timed) mark(e, CAT_OTHER, true);
     rc |= pl::launch_attention(ap, s);
     if (timed) mark(e, CAT_ATTN, true);
-    rc |= pl::launch_gemm(w.attn_out, lw.w_o, w.parts, n, d, qd, 0, e->sp_o, s);
+    rc |= pl::launch_gemm(w.attn_out, lw.w_o, w.parts, nullptr, n, d, qd, 0, e->ks_o, s);
     if (timed) mark(e, CAT_GEMM);
-    rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->sp_o, lw.g2, w.a, n, d, c.rms_eps, s);
+    rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->ks_o.splits, lw.g2, w.a, n, d, c.rms_eps, s);
     if (timed) mark(e, CAT_OTHER);
-    rc |= pl::launch_gemm(w.a, lw.w_gu, w.mid, n, 2 * c.d_ffn, d, 1, 1, s);
-    rc |= pl::launch_gemm(w.mid, lw.w_d, w.parts, n, d, c.d_ffn, 0, e->sp_d, s);
+    rc |= pl::launch_gemm(w.a, lw.w_gu, w.mid, w.parts, n, 2 * c.d_ffn, d, 1, e->ks_gu, s);
+    rc |= pl::launch_gemm(w.mid, lw.w_d, w.parts, nullptr, n, d, c.d_ffn, 0, e->ks_d, s);
     if (timed) mark(e, CAT_GEMM);
     const bf16_t *g_next = (l + 1 < c.n_layers) ? layer_weights(e, l + 1).g1 : gf;
-    rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->sp_d, g_next, w.a, n, d, c.rms_eps, s);
+    rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->ks_d.splits, g_next, w.a, n, d, c.rms_eps, s);
   }
   if (prefill) return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
   mark(e, CAT_OTHER);
-  rc |= pl::launch_gemm(w.a, lm, e->logits, n, c.vocab, d, 0, 1, s);
+  rc |= pl::launch_gemm(w.a, lm, e->logits, nullptr, n, c.vocab, d, 0, e->ks_lm, s);
   mark(e, CAT_GEMM);
   pl::SampleParams sp{};
   sp.logits = e->logits; sp.n = n; sp.vocab = c.vocab; sp.seq_id = w.m_seq_id(true);
@@ -1307,8 +1311,19 @@ int pl_kv_pack_host(uint16_t *pages_host, const int32_t *page_ids, const float *
 int pl_gemm_bf16(const void *x, const void *w, void *y, int32_t M, int32_t N, int32_t K, int32_t mode, int32_t splits,
                  void *stream) {
   if (!x || !w || !y) return fail(PL_E_INVAL, "NULL argument");
-  int rc = pl::launch_gemm((const bf16_t *)x, (const bf16_t *)w, y, M, N, K, mode, splits, (hipStream_t)stream);
+  if (mode == 1 && splits != 1) return fail(PL_E_INVAL, "the SwiGLU product takes splits = 1");
+  int rc = pl::launch_gemm((const bf16_t *)x, (const bf16_t *)w, y, nullptr, M, N, K, mode, pl::GemmSplit{splits, N, 1}, (hipStream_t)stream);
   if (rc == -1) return fail(PL_E_INVAL, "unsupported GEMM shape M=%d N=%d K=%d mode=%d splits=%d", M, N, K, mode, splits);
+  if (rc) return fail(PL_E_HIP, "GEMM launch failed");
+  return PL_OK;
+}
+
+int pl_debug_gemm_cfg(int32_t cfg, const void *x, const void *w, void *y, void *ws, int32_t M, int32_t N, int32_t K,
+                      int32_t mode, int32_t splits, int32_t n_begin, int32_t n_end, int32_t paired, void *stream) {
+  if (!x || !w || !y) return fail(PL_E_INVAL, "NULL argument");
+  int rc = pl::launch_gemm_cfg(cfg, (const bf16_t *)x, (const bf16_t *)w, y, (float *)ws, M, N, K, mode, splits, n_begin,
+                               n_end, paired != 0, (hipStream_t)stream);
+  if (rc == -1) return fail(PL_E_INVAL, "unsupported GEMM launch cfg=%d M=%d N=%d K=%d mode=%d splits=%d [%d, %d)", cfg, M, N, K, mode, splits, n_begin, n_end);
   if (rc) return fail(PL_E_HIP, "GEMM launch failed");
   return PL_OK;
 }

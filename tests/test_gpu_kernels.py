@@ -204,6 +204,49 @@ def test_gemm_swiglu_epilogue(M, F, K):
     assert ok, err
 
 
+CFG_TILES = {0: (32, 256), 1: (64, 256), 2: (128, 256), 3: (64, 128), 4: (128, 128), 5: (256, 128), 6: (64, 64),
+             7: (128, 64), 8: (32, 128), 9: (128, 64), 10: (256, 64)}
+
+
+@pytest.mark.parametrize("cfg", sorted(CFG_TILES))
+def test_every_gemm_tile_configuration_against_fp64(cfg):
+    """Each tile configuration of the kernel on shapes with several row tiles, a ragged last row tile,
+    a column range that starts and ends inside the matrix, with and without a K split; the SwiGLU
+    product also with its K split (partials + reduction)."""
+    rows, cols = CFG_TILES[cfg]
+    rng = np.random.default_rng(100 + cfg)
+    M, N, K = min(2 * rows + 7, 300), 5 * 128, 768
+    x = synth.bf16_round(rng.standard_normal((M, K), dtype=np.float32))
+    w = synth.bf16_round(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    xd, wd = dev_bf16(x), dev_bf16(pl.operand_order(w))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    for splits, nb, ne, paired in [(1, 0, N, False), (3, 128, N - 64, False), (1, 64, N, True)]:
+        y = torch.full((splits, M, N), float("nan"), device="cuda", dtype=torch.float32)
+        pl.pl_debug_gemm_cfg(cfg, xd.data_ptr(), wd.data_ptr(), y.data_ptr(), 0, M, N, K, 0, splits, nb, ne, paired, 0)
+        torch.cuda.synchronize()
+        got = to_np(y)
+        assert np.isnan(got[:, :, :nb]).all() and np.isnan(got[:, :, ne:]).all()       # nothing outside the range
+        tol = 1e-4 * (np.sqrt(K) * 0.05 + np.abs(ref[:, nb:ne]))
+        assert (np.abs(got[:, :, nb:ne].astype(np.float64).sum(0) - ref[:, nb:ne]) <= tol).all(), (splits, nb, ne)
+    if cfg in (6, 7, 8):                              # one 32-column tile per wavefront: no gate/up pair
+        with pytest.raises(pl.PlError):
+            pl.pl_debug_gemm_cfg(cfg, xd.data_ptr(), wd.data_ptr(), xd.data_ptr(), 0, M, N, K, 1, 1, 0, N, False, 0)
+        return
+    F = N // 2
+    gate = ref.reshape(M, N // 64, 2, 32)[:, :, 0].reshape(M, F)
+    up = ref.reshape(M, N // 64, 2, 32)[:, :, 1].reshape(M, F)
+    want = gate / (1.0 + np.exp(-gate)) * up
+    for splits, nb, ne in [(1, 0, N), (3, 0, N), (2, 128, N - 64)]:
+        mid = torch.full((M, F), float("nan"), device="cuda", dtype=torch.bfloat16)
+        ws = torch.empty(splits * M * (ne - nb), device="cuda", dtype=torch.float32)
+        pl.pl_debug_gemm_cfg(cfg, xd.data_ptr(), wd.data_ptr(), mid.data_ptr(), ws.data_ptr(), M, N, K, 1, splits, nb, ne, False, 0)
+        torch.cuda.synchronize()
+        got = to_np(mid)
+        assert np.isnan(got[:, :nb // 2]).all() and np.isnan(got[:, ne // 2:]).all()
+        ok, err = close(got[:, nb // 2:ne // 2], want[:, nb // 2:ne // 2], 2e-3, RTOL)
+        assert ok, (splits, nb, ne, err)
+
+
 def test_gemm_rejects_bad_shapes():
     t = torch.zeros(600 * 512, device="cuda", dtype=torch.bfloat16)
     for args in [(4, 64, 192, 0, 1), (0, 64, 256, 0, 1), (4, 64, 512, 0, 3), (4, 96, 256, 1, 1), (4, 64, 512, 1, 2),
