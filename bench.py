@@ -648,7 +648,8 @@ def main():
 
     d = {k: s1[k] - s0[k] for k in ("steps", "tokens_emitted", "slot_steps", "gpu_ms_total", "algorithmic_bytes",
                                      "attn_ms", "gemm_ms", "sample_ms", "other_ms", "attn_launches", "attn_kv_bytes",
-                                     "attn_shared_ms", "attn_shared_launches", "attn_shared_kv_bytes")}
+                                     "attn_shared_ms", "attn_shared_launches", "attn_shared_kv_bytes",
+                                     "host_enqueue_ms", "host_wait_ms")}
     sm = np.asarray(step_ms)
     med = float(np.median(sm))
     # swap stall: the step that contains the flip against the median of the 16 surrounding steps (None if no
@@ -679,6 +680,9 @@ def main():
                    "slot_utilisation": d["tokens_emitted"] / max(d["slot_steps"], 1),
                    "mean_batch": d["slot_steps"] / max(d["steps"], 1), "preempted": wl.preempted,
                    "kv_pool_tokens": s1["kv_pages_total"] * wl.page_tokens},
+        "host_ms_per_step": {"enqueue": d["host_enqueue_ms"] / max(d["steps"], 1), "wait_for_gpu": d["host_wait_ms"] / max(d["steps"], 1),
+                             "outside_the_engine": (1e3 * wall - d["host_enqueue_ms"] - d["host_wait_ms"]) / max(d["steps"], 1),
+                             "gpu_mean": d["gpu_ms_total"] / max(d["steps"], 1)},
         "gpu_ms_per_step_median": med, "gpu_ms_per_step_p99": float(np.percentile(sm, 99)),
         "step_hbm": {"algorithmic_bytes_per_step": d["algorithmic_bytes"] / max(d["steps"], 1),
                      "achieved_GBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6,

@@ -101,6 +101,9 @@ typedef struct {
    * cache-only pass (pl_prefill_async) was in flight, i.e. while the kernel shared the GPU */
   double attn_shared_ms, attn_shared_kv_bytes;
   uint64_t attn_shared_launches;
+  /* host time inside pl_decode_step, summed over steps: from entry until the step's work is enqueued,
+   * and from then until its results have arrived */
+  double host_enqueue_ms, host_wait_ms;
   /* batched prompt reading (pl_prefill); not part of steps / slot_steps / gpu_ms_total above */
   uint64_t prefill_passes, prefill_positions;
   double prefill_ms;

@@ -57,6 +57,7 @@ class Stats(C.Structure):
                 ("attn_ms", C.c_double), ("gemm_ms", C.c_double), ("sample_ms", C.c_double), ("other_ms", C.c_double),
                 ("attn_launches", C.c_uint64), ("gemm_launches", C.c_uint64), ("attn_kv_bytes", C.c_double),
                 ("attn_shared_ms", C.c_double), ("attn_shared_kv_bytes", C.c_double), ("attn_shared_launches", C.c_uint64),
+                ("host_enqueue_ms", C.c_double), ("host_wait_ms", C.c_double),
                 ("prefill_passes", C.c_uint64), ("prefill_positions", C.c_uint64), ("prefill_ms", C.c_double),
                 ("recompute_passes", C.c_uint64), ("recompute_positions", C.c_uint64), ("recompute_ms", C.c_double)]
 

@@ -46,5 +46,34 @@ def build(verbose: bool = False) -> str:
     return OUT
 
 
+class SanitizerUnavailable(RuntimeError):
+    pass
+
+
+def build_sanitized_driver(driver_c: str, out_dir: str) -> str:
+    """Link a C driver program against the library's objects with the HOST code of pl_engine.hip (all the
+    host logic) compiled under AddressSanitizer + UndefinedBehaviorSanitizer; device code is untouched.
+    Returns the path of the executable.  The kernel objects come from the ordinary build."""
+    if not all(os.path.exists(os.path.join(OBJ, s.replace(".hip", ".o"))) for s in SOURCES):
+        build()
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+    eng = os.path.join(out_dir, "pl_engine_san.o")
+    drv = os.path.join(out_dir, "driver.o")
+    exe = os.path.join(out_dir, "sanitize_driver")
+    try:
+        _run([HIPCC, *COMMON, *san, "-c", os.path.join(CSRC, "pl_engine.hip"), "-o", eng])
+        _run([HIPCC, "-x", "c", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+              "-c", driver_c, "-o", drv])
+        others = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES if s != "pl_engine.hip"]
+        _run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+              "-o", exe, drv, eng, *others])
+    except RuntimeError as ex:
+        if "sanitize" in str(ex) and ("unsupported" in str(ex) or "cannot find" in str(ex) or "not found" in str(ex)):
+            raise SanitizerUnavailable(str(ex)[-500:])
+        raise
+    return exe
+
+
 if __name__ == "__main__":
     build(verbose=True)

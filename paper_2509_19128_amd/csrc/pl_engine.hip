@@ -9,6 +9,7 @@
 #include "pl_common.h"
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -897,8 +898,13 @@ int32_t pl_num_active(const pl_engine *e) {
   return n;
 }
 
+static double now_ms() {
+  return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
 int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   if (!e || !out) return fail(PL_E_INVAL, "NULL argument");
+  const double t_enter = now_ms();
   if (!e->loaded) return fail(PL_E_STATE, "no weights loaded");
   const pl_model_cfg &c = e->cfg;
   // 1. validate: nothing below may fail half-way
@@ -1048,7 +1054,10 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     HIP_TRY(hipEventRecord(e->ev_b, s));
     HIP_TRY(hipMemcpyAsync(e->tok_h, e->tok_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(e->lp_h, e->lp_d, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+    const double t_enq = now_ms();
     HIP_TRY(hipStreamSynchronize(s));
+    e->st.host_enqueue_ms += t_enq - t_enter;
+    e->st.host_wait_ms += now_ms() - t_enq;
     HIP_TRY(hipEventElapsedTime(&out->step_ms, e->ev_a, e->ev_b));
     for (size_t i = 1; i < e->prof_n; ++i) {
       float ms = 0.f;
