@@ -143,7 +143,7 @@ struct pl_engine {
   // shape is the number of rows, the weight buffer, and the (rounded-up) grid bounds of the two
   // attention kernels; everything that changes from step to step is read from device buffers.
   struct StepGraph {
-    int n = 0, buf = 0, items = 0, multi = 0;
+    int n = 0, buf = 0, items = 0, multi = 0, set = 0;   // set: 0 decode step, 1 cache-only pass
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
     uint64_t last_use = 0;
@@ -432,7 +432,7 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
   return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
 }
 
-constexpr size_t MAX_STEP_GRAPHS = 24;
+constexpr size_t MAX_STEP_GRAPHS = 32;
 
 void drop_graph(pl_engine::StepGraph &g) {
   if (g.exec) (void)hipGraphExecDestroy(g.exec);
@@ -440,17 +440,19 @@ void drop_graph(pl_engine::StepGraph &g) {
   g = pl_engine::StepGraph{};
 }
 
-// Run the decode step's kernels for n rows on the decode stream: as the replay of a captured graph
-// when one may be used (no per-kernel timers), launch by launch otherwise.
-int run_step(pl_engine *e, pl_engine::Work &w, int n) {
-  if (!e->use_graphs || e->profile != 0) return enqueue_step(e, w, n);
+// Run the kernels of a decode step (or of a cache-only pass) for n rows on the work set's stream: as
+// the replay of a captured graph when one may be used (no per-kernel timers on the decode step), launch
+// by launch otherwise.
+int run_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) {
+  if (!e->use_graphs || (!prefill && e->profile != 0)) return enqueue_step(e, w, n, prefill);
+  const int set = prefill ? 1 : 0;
   // grid bounds of the attention kernels in coarse steps, so that few shapes occur; workgroups beyond
   // the lists' real lengths (which the kernels read from device memory) leave at once
   w.attn_items = std::min((w.attn_items + 63) / 64 * 64, n * e->attn_max_chunks);
   if (w.attn_multi) w.attn_multi = std::min((w.attn_multi + 15) / 16 * 16, n);
   pl_engine::StepGraph *g = nullptr;
   for (auto &x : e->graphs)
-    if (x.n == n && x.buf == e->active_buf && x.items == w.attn_items && x.multi == w.attn_multi) { g = &x; break; }
+    if (x.n == n && x.buf == e->active_buf && x.items == w.attn_items && x.multi == w.attn_multi && x.set == set) { g = &x; break; }
   if (!g) {
     if (e->graphs.size() >= MAX_STEP_GRAPHS) {   // evict the least recently used
       size_t lru = 0;
@@ -460,9 +462,9 @@ int run_step(pl_engine *e, pl_engine::Work &w, int n) {
       e->graphs.erase(e->graphs.begin() + lru);
     }
     pl_engine::StepGraph ng;
-    ng.n = n; ng.buf = e->active_buf; ng.items = w.attn_items; ng.multi = w.attn_multi;
+    ng.n = n; ng.buf = e->active_buf; ng.items = w.attn_items; ng.multi = w.attn_multi; ng.set = set;
     HIP_TRY(hipStreamBeginCapture(w.stream, hipStreamCaptureModeThreadLocal));
-    const int rc = enqueue_step(e, w, n);
+    const int rc = enqueue_step(e, w, n, prefill);
     const hipError_t ce = hipStreamEndCapture(w.stream, &ng.graph);
     if (rc || ce != hipSuccess) {
       drop_graph(ng);
@@ -606,7 +608,7 @@ int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::ve
         HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
       HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
       HIP_TRY(hipEventRecord(im.ev_begin, s));
-      int rc = enqueue_step(e, w, n, true);
+      int rc = run_step(e, w, n, true);
       if (rc) return rc;
       HIP_TRY(hipEventRecord(im.ev_end, s));
       im.pending = true;
