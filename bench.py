@@ -213,7 +213,7 @@ def stream_ceiling(torch, pl, nontemporal=False):
     return best
 
 
-PROFILE_OF = {"7b": "decode_step_7b_b256.md", "32b": "decode_step_32b_b64.md"}
+PROFILE_OF = {"7b": "decode_step_7b_b256.md", "32b": "decode_step_32b_b128.md"}
 
 
 def counter_traffic(workload, algorithmic_bytes):
@@ -439,6 +439,86 @@ def is_ess_study(args):
                                        "sample": f"first {k} sequences ({int(off[k])} tokens) of the same batch"}}))
 
 
+GEMM_CFG = [("32x256", 32, 256), ("64x256", 64, 256), ("128x256", 128, 256), ("64x128", 64, 128), ("128x128", 128, 128),
+            ("256x128", 256, 128), ("64x64", 64, 64), ("128x64", 128, 64), ("32x128", 32, 128), ("128x64P", 128, 64),
+            ("256x64P", 256, 64)]
+
+
+def gemm_sweep(args):
+    """Every tile configuration and K split of the GEMM kernel on the five products of one layer of the
+    workload's decoder (rows = its batch), through pl_debug_gemm_cfg.  Weights are cold (each measurement
+    walks 6-64 distinct copies of the matrix back to back, more bytes than any cache holds), the chip rests
+    4 ms before each measurement (sustained MFMA load lowers the clock, which would favour whatever is
+    measured first), the order is reshuffled every round; median of `--steps` rounds.  Prints one text table."""
+    import random
+    import torch
+    import paper_2509_19128_amd as pl
+
+    spec = WORKLOADS[args.workload]
+    m = synth.CONFIGS[spec["model"]]
+    M, d, F = spec["batch"], m.d_model, m.d_ffn
+    qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    products = [("QKV", qd + 2 * kvd, d, 0), ("O", d, qd, 0), ("gate/up + SwiGLU", 2 * F, d, 1), ("down", d, F, 0),
+                ("LM head", m.vocab, d, 0)]
+
+    def valid(K, sp):
+        total = K // 256
+        return 1 <= sp <= total and (sp - 1) * ((total + sp - 1) // sp) < total
+
+    print(f"# GEMM sweep, {args.workload} shape, M = {M} rows; us per launch (median of {args.steps} rounds), weights TB/s, TFLOP/s")
+    for tag, N, K, mode in products:
+        x = torch.randn(M, K, device="cuda").to(torch.bfloat16)
+        w = (torch.randn(N, K, device="cuda") * 0.02).to(torch.bfloat16)
+        wo = torch.from_numpy(pl.operand_order(w.view(torch.int16).cpu().numpy())).cuda()
+        copies = int(min(64, max(6, -(-700_000_000 // (N * K * 2)))))
+        wos = [wo] + [wo.clone() for _ in range(copies - 1)]
+        wide = N >= 32768
+        cands = []
+        for cfg, (name, rows, cols) in enumerate(GEMM_CFG):
+            rt = (M + rows - 1) // rows
+            if (mode == 1 and name in ("64x64", "128x64", "32x128")) or rt > 4 or (rows >= 2 * M and rows > 32):
+                continue
+            for sp in ([1] if wide else [1, 2, 3, 4, 6, 8, 9, 12]):
+                if not valid(K, sp) or ((N + cols - 1) // cols) * rt * sp > 4096:
+                    continue
+                for paired in ((False, True) if sp == 1 and rt > 1 else (False,)):
+                    cands.append((cfg, sp, paired))
+        spmax = max(c[1] for c in cands)
+        ws = torch.empty(spmax * M * N, device="cuda", dtype=torch.float32)
+        y = ws if mode == 0 else torch.zeros(M * N // 2, device="cuda", dtype=torch.bfloat16)
+        yw = torch.empty(spmax * M * N, device="cuda", dtype=torch.float32) if mode == 0 else ws
+        times, bad = {c: [] for c in cands}, set()
+        for r in range(args.steps + 1):
+            order = cands[:]
+            random.Random(r).shuffle(order)
+            for c in order:
+                if c in bad:
+                    continue
+                cfg, sp, paired = c
+                torch.cuda.synchronize()
+                time.sleep(0.004)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                try:
+                    a.record()
+                    for i in range(copies):
+                        pl.pl_debug_gemm_cfg(cfg, x.data_ptr(), wos[i].data_ptr(), (yw if mode == 0 else y).data_ptr(), ws.data_ptr(),
+                                             M, N, K, mode, sp, 0, N, paired, 0)
+                    b.record()
+                    torch.cuda.synchronize()
+                except pl.PlError:
+                    bad.add(c)
+                    continue
+                if r:
+                    times[c].append(a.elapsed_time(b) * 1e3 / copies)
+        res = sorted((float(np.median(times[c])), c) for c in cands if c not in bad)
+        print(f"== {tag}: N {N}, K {K}, weights {N * K * 2 / 1e6:.1f} MB, {copies} copies walked")
+        for t, (cfg, sp, paired) in res[:8]:
+            print(f"   {GEMM_CFG[cfg][0]:8s} slices {sp:2d}{' paired' if paired else '       '}: {t:7.1f} us  {N * K * 2 / t / 1e6:5.2f} TB/s  {2 * M * N * K / t / 1e6:5.0f} TFLOP/s")
+        sys.stdout.flush()
+        del wos, wo, w, ws, y, yw
+        torch.cuda.empty_cache()
+
+
 def attention_microbench(args):
     """One decode-attention step over a paged bf16 cache: batch 512, 28 q / 4 kv heads, head_dim 128,
     contexts lognormal(4096) clipped to [128, 16384], q/K/V ~ N(0,1); median over `--steps` launches (the
@@ -509,6 +589,8 @@ def main():
                     help="instead of the benchmark line: the decode-attention microbenchmark (batch 512, one step)")
     ap.add_argument("--is-ess", action="store_true",
                     help="instead of the benchmark line: time the importance-weight / ESS reduction on one optimizer batch")
+    ap.add_argument("--gemm-sweep", action="store_true",
+                    help="instead of the benchmark line: every GEMM tile configuration and K split on the workload's five products")
     ap.add_argument("--batch-study", action="store_true",
                     help="instead of the benchmark line: throughput against batch size and a replay of a stage without refill")
     ap.add_argument("--gpus", type=int, default=1)
@@ -530,6 +612,8 @@ def main():
               "and are not launched here (--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
 
+    if args.gemm_sweep:
+        return gemm_sweep(args)
     if args.batch_study:
         return batch_study(args)
     if args.is_ess:
