@@ -43,6 +43,8 @@ typedef enum {
 #define PL_SWAP_WAIT 1u  /* the next step waits for the staging copy, then flips                  */
 #define PL_SWAP_RECOMPUTE_KV 2u /* or-ed in: at the flip, rebuild every sequence's cache under the new weights */
 #define PL_DEVICE_NONE (-1) /* bookkeeping-only engine: no GPU is touched, no token is computed  */
+#define PL_BF16 0 /* the engine proper: bf16 weights, KV cache and activations, fp32 accumulation   */
+#define PL_F32 1  /* test build: everything in fp32 through plain kernels (see pl_model_cfg.dtype) */
 
 typedef struct pl_engine pl_engine;
 
@@ -64,6 +66,13 @@ typedef struct {
                                overwrite the only buffer and always block */
   uint64_t seed;          /* sampler key */
   int32_t device;         /* HIP device ordinal, or PL_DEVICE_NONE */
+  int32_t dtype;          /* PL_BF16 (0), or PL_F32: the test build, in which weights, KV cache and
+                             activations are fp32 and every step runs through plain, untuned kernels, so
+                             that the engine around them (slots, pages, positions, head mapping, update
+                             protocol, sampler keying) can be held to 1e-4 against the oracle.  Its blob
+                             has the same tensors in the same order, 4 bytes per element, every matrix
+                             row-major [out, in], "l<l>.w_gu" = all gate rows then all up rows
+                             (pl_pack_weights produces it).  Same calls, same semantics; slow. */
 } pl_model_cfg;
 
 /* Result of one decode step: one entry per occupied slot, in slot order.  Arrays are caller
@@ -142,7 +151,8 @@ int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t
 int64_t pl_weight_nbytes(const pl_engine *e);
 
 /* Host helper (layout only, no device access): write one source tensor into its place in a host
- * image `blob` (pl_weight_nbytes bytes) of the flat blob described above.  `name` is "embed", "gf",
+ * image `blob` (pl_weight_nbytes bytes) of the flat blob described above (or of the fp32 test
+ * build's blob, whose sources must be fp32).  `name` is "embed", "gf",
  * "lm_head", or "l<l>.<t>" with t one of g1, g2 (gains, [d]), wq [Hq hd, d], wk, wv [Hkv hd, d],
  * wo [d, Hq hd], wg, wu [F, d], wd [d, F]; `src` is the tensor row-major [out_features, in_features],
  * fp32 if src_is_f32 (rounded to bf16, nearest even) or bf16 bit patterns otherwise.  The row

@@ -8,7 +8,7 @@ import numpy as np
 
 __all__ = [
     "PL_OK", "PL_E_INVAL", "PL_E_NOSLOT", "PL_E_NOKV", "PL_E_BUSY", "PL_E_STATE", "PL_E_CTX", "PL_E_HIP",
-    "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_SWAP_RECOMPUTE_KV", "PL_DEVICE_NONE", "PlError", "ModelCfg", "StepOut", "Stats",
+    "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_SWAP_RECOMPUTE_KV", "PL_DEVICE_NONE", "PL_BF16", "PL_F32", "PlError", "ModelCfg", "StepOut", "Stats",
     "lib", "library_path", "Engine", "operand_order", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
     "pl_gemm_bf16", "pl_debug_gemm_cfg", "pl_sample", "pl_sample_static", "pl_sample_workspace_bytes", "pl_debug_stream_read", "pl_is_ess", "EXPORTS",
 ]
@@ -16,6 +16,7 @@ __all__ = [
 PL_OK, PL_E_INVAL, PL_E_NOSLOT, PL_E_NOKV, PL_E_BUSY, PL_E_STATE, PL_E_CTX, PL_E_HIP, PL_E_NOMEM = 0, -1, -2, -3, -4, -5, -6, -7, -8
 PL_SWAP_ASYNC, PL_SWAP_WAIT, PL_SWAP_RECOMPUTE_KV = 0, 1, 2
 PL_DEVICE_NONE = -1
+PL_BF16, PL_F32 = 0, 1
 
 # every symbol include/pl.h declares
 EXPORTS = [
@@ -38,7 +39,7 @@ class ModelCfg(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("max_batch", C.c_int32),
                 ("max_context", C.c_int32), ("kv_pool_tokens", C.c_int64), ("kv_page_tokens", C.c_int32),
-                ("n_weight_buffers", C.c_int32), ("seed", C.c_uint64), ("device", C.c_int32)]
+                ("n_weight_buffers", C.c_int32), ("seed", C.c_uint64), ("device", C.c_int32), ("dtype", C.c_int32)]
 
 
 class StepOut(C.Structure):
@@ -147,10 +148,10 @@ class Engine:
 
     def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, max_batch,
                  max_context, kv_pool_tokens, rope_theta=1.0e4, rms_eps=1.0e-6, kv_page_tokens=0,
-                 n_weight_buffers=2, seed=0, device=0):
+                 n_weight_buffers=2, seed=0, device=0, dtype=PL_BF16):
         self.cfg = ModelCfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rope_theta,
                             rms_eps, max_batch, max_context, kv_pool_tokens, kv_page_tokens, n_weight_buffers,
-                            seed, device)
+                            seed, device, dtype)
         self._h = C.c_void_p()
         _check(lib().pl_create(C.byref(self.cfg), C.byref(self._h)))
         B = max_batch
@@ -194,6 +195,8 @@ class Engine:
         """Flat uint16 (bf16 bits) blob from per-tensor fp32 arrays named wq/wk/wv/wo/wg/wu/wd/g1/g2
         per layer plus embed/gf/lm_head; `to_bits` converts fp32 -> bf16 bit patterns.  Row
         concatenation, the 32-row gate/up interleave and the operand ordering are layout only."""
+        if self.cfg.dtype == PL_F32:
+            return self.pack_weights_c(tensors)          # fp32 test build: row-major fp32, no bf16 conversion
         blob = np.empty(self.weight_nbytes() // 2, np.uint16)
         for name, off, (r, c) in self.weight_layout():
             if name.endswith("w_qkv"):
@@ -216,8 +219,10 @@ class Engine:
         return blob
 
     def pack_weights_c(self, tensors):
-        """The same blob through the library's host helper pl_pack_weights (fp32 sources)."""
-        blob = np.zeros(self.weight_nbytes() // 2, np.uint16)
+        """The blob through the library's host helper pl_pack_weights (fp32 sources): uint16 bf16 bit
+        patterns, or float32 for an engine of the fp32 test build."""
+        f32 = self.cfg.dtype == PL_F32
+        blob = np.zeros(self.weight_nbytes() // (4 if f32 else 2), np.float32 if f32 else np.uint16)
         for name, w in tensors.items():
             w = np.ascontiguousarray(w, np.float32)
             _check(lib().pl_pack_weights(self._h, name.encode(), _np_ptr(w), 1, _np_ptr(blob)))

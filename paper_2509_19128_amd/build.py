@@ -18,7 +18,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-
 # the sampler's float32 decision must not be re-associated or fused
 PER_FILE = {"kernels_sample.hip": ["-ffp-contract=off"]}
 SOURCES = ["pl_engine.hip", "kernels_attn.hip", "kernels_gemm.hip", "kernels_misc.hip", "kernels_sample.hip",
-           "kernels_is.hip"]
+           "kernels_is.hip", "kernels_f32.hip"]
 
 
 def _run(cmd):

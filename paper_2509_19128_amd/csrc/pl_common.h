@@ -93,6 +93,17 @@ int launch_rope_tables(const int32_t *pos, float *cs, int32_t *ctx_len, int n, i
 int launch_rope_append(const float *qkv, int splits, const float *cs, const int32_t *pos,
                        const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out, bf16_t *kv_layer,
                        int n, int Hq, int Hkv, int hd, int page_tokens, int pages_per_seq, hipStream_t s);
+// fp32 test build (kernels_f32.hip)
+int f32_launch_norm(const float *embed, const int32_t *input_tok, int vocab, const float *y, const float *g, float *h,
+                    float *a, int n, int d, float eps, hipStream_t s);
+int f32_launch_gemm(const float *x, const float *w, float *y, int M, int N, int K, hipStream_t s);
+int f32_launch_swiglu(const float *gu, float *mid, int M, int F, hipStream_t s);
+int f32_launch_rope_append(const float *qkv, const float *cs, const int32_t *pos, const int32_t *row_slot,
+                           const int32_t *page_table, float *q_out, float *kv_layer, int n, int Hq, int Hkv, int hd,
+                           int page_tokens, int pages_per_seq, hipStream_t s);
+int f32_launch_attention(const float *q, const float *kv_layer, const int32_t *page_table, const int32_t *pos,
+                         const int32_t *row_slot, float *out, int n, int Hq, int Hkv, int hd, int page_tokens,
+                         int pages_per_seq, hipStream_t s);
 int64_t launch_stream_read(const void *p, int64_t nbytes, uint32_t *sink, bool nontemporal, hipStream_t s);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);
 int launch_is_ess(const float *lp_pi, const float *lp_mu, const int64_t *offsets, int n_seq, double c, float *w_out,

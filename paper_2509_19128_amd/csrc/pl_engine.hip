@@ -80,7 +80,9 @@ struct pl_engine {
   // weights
   std::vector<Tensor> layout;
   int64_t blob_elems = 0;
-  bf16_t *wbuf[2] = {nullptr, nullptr};
+  bool f32 = false;   // the fp32 test build
+  int esz = 2;        // bytes per stored element (weights, KV, activations)
+  char *wbuf[2] = {nullptr, nullptr};
   int active_buf = 0;
   uint32_t version = 0;
   bool loaded = false;
@@ -88,7 +90,7 @@ struct pl_engine {
   uint32_t staged_version = 0;
   hipEvent_t ev_staged = nullptr, ev_copy0 = nullptr;
   // kv
-  bf16_t *kv_pool = nullptr;
+  char *kv_pool = nullptr;   // bf16 pages in operand order, or fp32 pages of the test build
   std::vector<int32_t> free_pages;
   int32_t *pt_h = nullptr, *pt_d = nullptr;
   bool pt_dirty = false;
@@ -163,11 +165,6 @@ struct pl_engine {
   pl_stats st{};
   int64_t streamed_weight_bytes = 0;
 
-  const bf16_t *wptr(int buf, const char *name) const {
-    for (auto &t : layout)
-      if (t.name == name) return wbuf[buf] + t.offset;
-    return nullptr;
-  }
 };
 
 namespace {
@@ -193,7 +190,7 @@ void build_layout(pl_engine *e) {
   add("gf", d, 1);
   add("lm_head", c.vocab, d);
   e->blob_elems = off;
-  e->streamed_weight_bytes = 2 * (off - (int64_t)c.vocab * d);
+  e->streamed_weight_bytes = (int64_t)e->esz * (off - (int64_t)c.vocab * d);
 }
 
 int check_cfg(const pl_model_cfg &c) {
@@ -210,6 +207,7 @@ int check_cfg(const pl_model_cfg &c) {
   if (c.kv_page_tokens < 0 || c.kv_page_tokens % 32) return fail(PL_E_INVAL, "kv_page_tokens must be a multiple of 32");
   if (c.n_weight_buffers != 1 && c.n_weight_buffers != 2) return fail(PL_E_INVAL, "n_weight_buffers must be 1 or 2");
   if (!(c.rope_theta > 0) || !(c.rms_eps >= 0)) return fail(PL_E_INVAL, "bad rope_theta / rms_eps");
+  if (c.dtype != PL_BF16 && c.dtype != PL_F32) return fail(PL_E_INVAL, "dtype must be PL_BF16 or PL_F32");
   if (c.kv_pool_tokens < 0) return fail(PL_E_INVAL, "kv_pool_tokens must be >= 0 (0 = size the pool from free memory)");
   // the GEMM kernels address a matrix through one 32-bit buffer descriptor
   const int64_t qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
@@ -243,15 +241,16 @@ int dev_alloc(T **p, int64_t n_elems) {
 int alloc_work(pl_engine *e, pl_engine::Work &w, int64_t R, int64_t parts_elems, bool pinned_image) {
   const pl_model_cfg &c = e->cfg;
   const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim;
+  const int64_t wide = e->esz / 2;   // the activation buffers are declared bf16; the fp32 build needs twice the bytes
   int rc;
   w.rows_cap = (int)R;
   if ((rc = dev_alloc(&w.meta_d, e->meta_bytes))) return rc;
   if ((rc = dev_alloc(&w.h, R * d))) return rc;
-  if ((rc = dev_alloc(&w.a, R * d))) return rc;
+  if ((rc = dev_alloc(&w.a, R * d * wide))) return rc;
   if ((rc = dev_alloc(&w.parts, parts_elems))) return rc;
-  if ((rc = dev_alloc(&w.q_rot, R * qd))) return rc;
-  if ((rc = dev_alloc(&w.attn_out, R * qd))) return rc;
-  if ((rc = dev_alloc(&w.mid, R * c.d_ffn))) return rc;
+  if ((rc = dev_alloc(&w.q_rot, R * qd * wide))) return rc;
+  if ((rc = dev_alloc(&w.attn_out, R * qd * wide))) return rc;
+  if ((rc = dev_alloc(&w.mid, R * c.d_ffn * wide))) return rc;
   if ((rc = dev_alloc(&w.cs, R * c.head_dim))) return rc;
   if ((rc = dev_alloc(&w.ctx_len, R))) return rc;
   const int64_t np = R * c.n_kv_heads * e->attn_max_chunks * e->G;
@@ -286,7 +285,7 @@ int alloc_device(pl_engine *e) {
   HIP_TRY(hipEventCreateWithFlags(&e->ev_pre_last, hipEventDisableTiming));
   int rc;
   for (int b = 0; b < c.n_weight_buffers; ++b)
-    if ((rc = dev_alloc(&e->wbuf[b], e->blob_elems))) return rc;
+    if ((rc = dev_alloc(&e->wbuf[b], e->blob_elems * e->esz))) return rc;
   const int B = c.max_batch;
   const int64_t d = c.d_model, qd = (int64_t)c.n_q_heads * c.head_dim, kvd = (int64_t)c.n_kv_heads * c.head_dim;
   const int64_t wq = qd + 2 * kvd;
@@ -297,8 +296,9 @@ int alloc_device(pl_engine *e) {
   e->ks_d = pl::gemm_pick_split(B, (int)d, c.d_ffn, 0);
   e->ks_lm = pl::GemmSplit{1, c.vocab, 1};
   const int64_t R = e->rows_cap;   // rows of the activation buffers (cache-only passes take up to 256 rows)
-  const int64_t parts = std::max(std::max(std::max(e->ks_qkv.splits * wq, e->ks_o.splits * d), e->ks_d.splits * d) * R,
-                                 pl::gemm_workspace_elems((int)R, 2 * c.d_ffn, e->ks_gu));
+  int64_t parts = std::max(std::max(std::max(e->ks_qkv.splits * wq, e->ks_o.splits * d), e->ks_d.splits * d) * R,
+                           pl::gemm_workspace_elems((int)R, 2 * c.d_ffn, e->ks_gu));
+  if (e->f32) parts = R * std::max(wq, 2 * (int64_t)c.d_ffn);   // the fp32 build keeps whole products there
   // the chunk length is fixed by max_batch alone, so a sequence's attention result never depends on
   // how many rows a pass holds
   e->attn_chunk = pl::attention_chunk_tokens(B, c.n_kv_heads, c.max_context);
@@ -325,7 +325,7 @@ int alloc_device(pl_engine *e) {
   if (e->n_pages == 0) {
     size_t free_b = 0, total_b = 0;
     HIP_TRY(hipMemGetInfo(&free_b, &total_b));
-    const int64_t page_bytes = e->page_stride * 2 * std::max(c.n_layers, 1);
+    const int64_t page_bytes = e->page_stride * e->esz * std::max(c.n_layers, 1);
     const int64_t avail = (int64_t)free_b - KV_AUTO_RESERVE_BYTES;
     const int64_t most = (int64_t)B * e->pages_per_seq;
     e->n_pages = std::min(avail > 0 ? avail / page_bytes : 0, most);
@@ -333,10 +333,10 @@ int alloc_device(pl_engine *e) {
     set_pool_pages(e, e->n_pages);
   }
   const int64_t pool_elems = e->layer_stride * c.n_layers;
-  if ((rc = dev_alloc(&e->kv_pool, pool_elems))) return rc;
+  if ((rc = dev_alloc(&e->kv_pool, pool_elems * e->esz))) return rc;
   // Every position a kernel may touch must hold a finite value: masked soft-max weights are
   // exactly 0, and 0 * finite stays 0.
-  HIP_TRY(hipMemsetAsync(e->kv_pool, 0, (size_t)pool_elems * 2, e->s_dec));
+  HIP_TRY(hipMemsetAsync(e->kv_pool, 0, (size_t)pool_elems * e->esz, e->s_dec));
   HIP_TRY(hipHostMalloc((void **)&e->pt_h, (size_t)B * e->pages_per_seq * 4, hipHostMallocDefault));
   HIP_TRY(hipHostMalloc((void **)&e->tok_h, (size_t)B * 4, hipHostMallocDefault));
   HIP_TRY(hipHostMalloc((void **)&e->lp_h, (size_t)B * 4, hipHostMallocDefault));
@@ -346,7 +346,7 @@ int alloc_device(pl_engine *e) {
 }
 
 LayerW layer_weights(const pl_engine *e, int l) {
-  const bf16_t *base = e->wbuf[e->active_buf];
+  const bf16_t *base = (const bf16_t *)e->wbuf[e->active_buf];
   const Tensor *t = &e->layout[1 + (size_t)l * 6];
   return LayerW{base + t[0].offset, base + t[1].offset, base + t[2].offset,
                 base + t[3].offset, base + t[4].offset, base + t[5].offset};
@@ -368,14 +368,57 @@ void mark(pl_engine *e, int cat, bool attention_edge = false) {
   (void)hipEventRecord(e->prof_ev[e->prof_n++], e->s_dec);
 }
 
+// The same step in the fp32 test build: plain kernels, whole products in `parts`, no K split, no
+// attention chunks.  Same order of operations as the definition: embed, per layer norm, q|k|v, rotary,
+// append, attention, +W_o, norm, SwiGLU, +W_d, final norm, LM head, sampler.
+int enqueue_step_f32(pl_engine *e, pl_engine::Work &w, int n, bool prefill) {
+  const pl_model_cfg &c = e->cfg;
+  hipStream_t s = w.stream;
+  if (!prefill) e->prof_n = 0;
+  const float *base = (const float *)e->wbuf[e->active_buf];
+  auto T = [&](size_t i) { return base + e->layout[i].offset; };
+  const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, wq = qd + 2 * kvd;
+  const size_t last = e->layout.size() - 1;
+  float *a = (float *)w.a, *q_rot = (float *)w.q_rot, *attn_out = (float *)w.attn_out, *mid = (float *)w.mid;
+  int rc = 0;
+  rc |= pl::launch_rope_tables(w.m_pos(true), w.cs, w.ctx_len, n, c.head_dim, c.rope_theta, s);
+  rc |= pl::f32_launch_norm(T(0), w.m_input(true), c.vocab, nullptr, c.n_layers ? T(1) : T(last - 1), w.h, a, n, d, c.rms_eps, s);
+  for (int l = 0; l < c.n_layers && !rc; ++l) {
+    const size_t t0 = 1 + (size_t)l * 6;   // g1, w_qkv, w_o, g2, w_gu, w_d
+    float *kv_layer = (float *)e->kv_pool + (int64_t)l * e->layer_stride;
+    rc |= pl::f32_launch_gemm(a, T(t0 + 1), w.parts, n, wq, d, s);
+    rc |= pl::f32_launch_rope_append(w.parts, w.cs, w.m_pos(true), w.m_row_slot(true), e->pt_d, q_rot, kv_layer, n,
+                                     c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens, e->pages_per_seq, s);
+    if (prefill && l + 1 == c.n_layers) break;
+    rc |= pl::f32_launch_attention(q_rot, kv_layer, e->pt_d, w.m_pos(true), w.m_row_slot(true), attn_out, n, c.n_q_heads,
+                                   c.n_kv_heads, c.head_dim, e->page_tokens, e->pages_per_seq, s);
+    rc |= pl::f32_launch_gemm(attn_out, T(t0 + 2), w.parts, n, d, qd, s);
+    rc |= pl::f32_launch_norm(nullptr, nullptr, 0, w.parts, T(t0 + 3), w.h, a, n, d, c.rms_eps, s);
+    rc |= pl::f32_launch_gemm(a, T(t0 + 4), w.parts, n, 2 * c.d_ffn, d, s);
+    rc |= pl::f32_launch_swiglu(w.parts, mid, n, c.d_ffn, s);
+    rc |= pl::f32_launch_gemm(mid, T(t0 + 5), w.parts, n, d, c.d_ffn, s);
+    rc |= pl::f32_launch_norm(nullptr, nullptr, 0, w.parts, l + 1 < c.n_layers ? T(t0 + 6) : T(last - 1), w.h, a, n, d,
+                              c.rms_eps, s);
+  }
+  if (prefill) return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
+  rc |= pl::f32_launch_gemm(a, T(last), e->logits, n, c.vocab, d, s);
+  pl::SampleParams sp{};
+  sp.logits = e->logits; sp.n = n; sp.vocab = c.vocab; sp.seq_id = w.m_seq_id(true);
+  sp.position = w.m_pos(true); sp.inv_t = w.m_inv_t(true); sp.forced = w.m_forced(true);
+  sp.seed = c.seed; sp.token = e->tok_d; sp.logprob = e->lp_d; sp.workspace = e->samp_ws;
+  rc |= pl::launch_sample(sp, s);
+  return rc ? fail(PL_E_HIP, "kernel launch failed: %s", hipGetErrorString(hipGetLastError())) : PL_OK;
+}
+
 // prefill: cache-only pass; only the keys and values the rows leave in the cache are wanted, so the
 // last layer stops after its append and there is no LM head or sampler.  Runs on the work set's stream.
 int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) {
   const pl_model_cfg &c = e->cfg;
   hipStream_t s = w.stream;
+  if (e->f32) return enqueue_step_f32(e, w, n, prefill);
   const bool timed = !prefill;   // the per-group timers describe decode steps only
   if (timed) { e->prof_n = 0; mark(e, CAT_OTHER); }
-  const bf16_t *base = e->wbuf[e->active_buf];
+  const bf16_t *base = (const bf16_t *)e->wbuf[e->active_buf];
   const int d = c.d_model, qd = c.n_q_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim, wq = qd + 2 * kvd;
   const bf16_t *embed = base + e->layout.front().offset;
   const bf16_t *gf = base + e->layout[e->layout.size() - 2].offset;
@@ -389,7 +432,7 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
                                  d, c.vocab, c.rms_eps, s);
   for (int l = 0; l < c.n_layers && !rc; ++l) {
     const LayerW lw = layer_weights(e, l);
-    bf16_t *kv_layer = e->kv_pool + (int64_t)l * e->layer_stride;
+    bf16_t *kv_layer = (bf16_t *)e->kv_pool + (int64_t)l * e->layer_stride;
     if (timed) mark(e, CAT_OTHER);
     rc |= pl::launch_gemm(w.a, lw.w_qkv, w.parts, nullptr, n, wq, d, 0, e->ks_qkv, s);
     if (timed) mark(e, CAT_GEMM);
@@ -659,6 +702,8 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
   if (!e) return fail(PL_E_NOMEM, "out of host memory");
   e->cfg = *cfg;
   e->dry = cfg->device == PL_DEVICE_NONE;
+  e->f32 = cfg->dtype == PL_F32;
+  e->esz = e->f32 ? 4 : 2;
   e->G = cfg->n_q_heads / cfg->n_kv_heads;
   e->page_tokens = cfg->kv_page_tokens ? cfg->kv_page_tokens : 128;
   e->pages_per_seq = (cfg->max_context + e->page_tokens - 1) / e->page_tokens;
@@ -740,7 +785,7 @@ int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t
   return PL_OK;
 }
 
-int64_t pl_weight_nbytes(const pl_engine *e) { return e ? e->blob_elems * 2 : 0; }
+int64_t pl_weight_nbytes(const pl_engine *e) { return e ? e->blob_elems * e->esz : 0; }
 
 int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32_t src_is_f32, void *blob) {
   if (!e || !name || !src || !blob) return fail(PL_E_INVAL, "NULL argument");
@@ -770,6 +815,12 @@ int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32
   for (const Tensor &x : e->layout)
     if (x.name == target) { t = &x; break; }
   if (!t) return fail(PL_E_INVAL, "unknown tensor '%s'", name);
+  if (e->f32) {   // test build: fp32, row-major, rows placed at row0 (gate rows first, then up rows)
+    if (!src_is_f32) return fail(PL_E_INVAL, "the fp32 build packs fp32 sources");
+    if (interleave == 1) row0 = c.d_ffn;
+    memcpy((float *)blob + t->offset + row0 * cols, src, (size_t)(rows * cols) * 4);
+    return PL_OK;
+  }
   uint16_t *dst = (uint16_t *)blob + t->offset;
   auto bits = [&](int64_t i) -> uint16_t {
     return src_is_f32 ? f32_to_bf16_bits(((const float *)src)[i]) : ((const uint16_t *)src)[i];
@@ -791,7 +842,7 @@ int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32
 
 int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes) {
   if (!e || !src) return fail(PL_E_INVAL, "NULL argument");
-  if (nbytes != e->blob_elems * 2) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * 2));
+  if (nbytes != e->blob_elems * e->esz) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * e->esz));
   if (e->staged) return fail(PL_E_BUSY, "a weight update is staged");
   if (!e->dry) {
     HIP_TRY(hipSetDevice(e->cfg.device));
@@ -810,7 +861,7 @@ int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flag
   if (flags & PL_SWAP_RECOMPUTE_KV)
     for (const Seq &q : e->seqs)
       if (q.active && !q.hist_known) return fail(PL_E_STATE, "a sequence was admitted without its token history; its cache cannot be recomputed");
-  if (nbytes != e->blob_elems * 2) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * 2));
+  if (nbytes != e->blob_elems * e->esz) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * e->esz));
   if (!e->loaded) return fail(PL_E_STATE, "no weights loaded yet");
   if (e->staged) return fail(PL_E_BUSY, "the previous weight update is not active yet");
   e->staged_version = e->version + 1;
@@ -986,7 +1037,8 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       // Nothing may read the old weights after the flip: with every element a bf16 NaN, a kernel that
       // still does shows up in the logits.  The next staging copy overwrites the buffer; it cannot start
       // before this step has ended (steps are synchronous), so the fill needs no further ordering.
-      if (pl::launch_fill_u32((uint32_t *)e->wbuf[e->active_buf ^ 1], 0x7FC07FC0u, e->blob_elems / 2, e->s_dec))
+      if (pl::launch_fill_u32((uint32_t *)e->wbuf[e->active_buf ^ 1], e->f32 ? 0x7FC00000u : 0x7FC07FC0u,
+                              e->blob_elems * e->esz / 4, e->s_dec))
         return fail(PL_E_HIP, "fill launch failed");
     }
     if (!e->staged && !e->dry) {
@@ -1107,7 +1159,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
   e->st.steps++;
   e->st.slot_steps += n;
   e->st.gpu_ms_total += out->step_ms;
-  const double kvb = 2.0 * c.n_layers * c.n_kv_heads * c.head_dim * 2.0;
+  const double kvb = 2.0 * c.n_layers * c.n_kv_heads * c.head_dim * e->esz;
   e->st.algorithmic_bytes += (double)e->streamed_weight_bytes + (kv_tokens + n) * kvb;
   return PL_OK;
 }
@@ -1190,9 +1242,27 @@ static int kv_xfer(pl_engine *e, int32_t slot, int32_t layer, float *k, float *v
   HIP_TRY(hipStreamSynchronize(e->s_dec));
   HIP_TRY(hipStreamSynchronize(e->wk[1].stream));
   const int hd = c.head_dim, Hkv = c.n_kv_heads, ptok = e->page_tokens;
+  if (e->f32) {   // fp32 pages: [kv head][K | V][token][hd]
+    std::vector<float> img((size_t)e->page_stride);
+    for (int p0 = 0; p0 < n_ctx; p0 += ptok) {
+      float *dev = (float *)e->kv_pool + (int64_t)layer * e->layer_stride + (int64_t)q.pages[p0 / ptok] * e->page_stride;
+      HIP_TRY(hipMemcpy(img.data(), dev, img.size() * 4, hipMemcpyDeviceToHost));
+      const int cnt = std::min(ptok, n_ctx - p0);
+      for (int t = 0; t < cnt; ++t)
+        for (int g = 0; g < Hkv; ++g)
+          for (int d = 0; d < hd; ++d) {
+            const int64_t ci = ((int64_t)(p0 + t) * Hkv + g) * hd + d;
+            float *kb = img.data() + ((int64_t)g * 2 * ptok + t) * hd + d, *vb = kb + (int64_t)ptok * hd;
+            if (write) { *kb = k_in[ci]; *vb = v_in[ci]; }
+            else { k[ci] = *kb; v[ci] = *vb; }
+          }
+      if (write) HIP_TRY(hipMemcpy(dev, img.data(), img.size() * 4, hipMemcpyHostToDevice));
+    }
+    return PL_OK;
+  }
   std::vector<uint16_t> img((size_t)e->page_stride);
   for (int p0 = 0; p0 < n_ctx; p0 += ptok) {
-    bf16_t *dev = e->kv_pool + (int64_t)layer * e->layer_stride + (int64_t)q.pages[p0 / ptok] * e->page_stride;
+    bf16_t *dev = (bf16_t *)e->kv_pool + (int64_t)layer * e->layer_stride + (int64_t)q.pages[p0 / ptok] * e->page_stride;
     HIP_TRY(hipMemcpy(img.data(), dev, img.size() * 2, hipMemcpyDeviceToHost));
     const int cnt = std::min(ptok, n_ctx - p0);
     for (int t = 0; t < cnt; ++t)
@@ -1246,7 +1316,7 @@ int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes) {
   if (!e || !device_ptr || !nbytes) return fail(PL_E_INVAL, "NULL argument");
   if (e->dry) return fail(PL_E_STATE, "bookkeeping-only engine holds no KV");
   *device_ptr = e->kv_pool;
-  *nbytes = e->layer_stride * e->cfg.n_layers * 2;
+  *nbytes = e->layer_stride * e->cfg.n_layers * e->esz;
   return PL_OK;
 }
 

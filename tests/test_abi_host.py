@@ -332,3 +332,24 @@ def test_background_prompt_reading_bookkeeping():
     e.retire_sequence(s2)                     # retiring a slot that is still reading is allowed
     assert e.num_active() == 2
     assert e.prefill_async(s1) == 0           # nothing left to read
+
+
+def test_fp32_test_build_blob_is_row_major_fp32():
+    e = _engine(dtype=pl.PL_F32)
+    W = synth.make_weights(M, 13)
+    assert e.weight_nbytes() == 4 * (M.streamed_params() + M.vocab * M.d_model)
+    blob = e.pack_weights(W, None)
+    assert blob.dtype == np.float32
+    d = dict((n, (o, s)) for n, o, s in e.weight_layout())
+    o, (r, c) = d["l1.w_qkv"]
+    assert np.array_equal(blob[o:o + r * c].reshape(r, c), np.concatenate([W["l1.wq"], W["l1.wk"], W["l1.wv"]]))
+    o, (r, c) = d["l0.w_gu"]
+    assert np.array_equal(blob[o:o + r * c].reshape(r, c), np.concatenate([W["l0.wg"], W["l0.wu"]]))
+    o, (r, c) = d["l1.g2"]
+    assert np.array_equal(blob[o:o + r], W["l1.g2"])
+    e.load_weights(blob)
+    e.add_sequence(1, [1, 2, 3], 2)
+    assert e.decode_step()["n"] == 1
+    with pytest.raises(pl.PlError) as ex:
+        _engine(dtype=7)
+    assert ex.value.code == pl.PL_E_INVAL
