@@ -333,13 +333,14 @@ int gemm_pick_splits(int M, int N, int K) {
       if (splits_valid(K, sp)) best = sp;
     return best;
   };
+  if (M <= 32 && N < 16384) return largest((N + 127) / 128, 256);               // 32 x 128 tiles
   if (M <= 64 && N < 16384) return largest((N + 63) / 64, 256);                 // 64 x 64 tiles
   if (M <= 128) return largest((N + 255) / 256, 256);                           // 128 x 256 tiles
-  if (M <= 256 && K <= 4096) {   // two slices of 128 x 64 tiles while those fit the chip at once, else three of 128 x 128
-    if (((N + 63) / 64) * 4 <= 256 || !splits_valid(K, 3)) return splits_valid(K, 2) ? 2 : 1;
-    return 3;
-  }
-  if (M <= 256) return largest(((N + 255) / 256) * 2, 232);                     // 128 x 256 tiles
+  // 129..256 rows: at these rows two, three or four slices of the short-K products (QKV, O) and eight or
+  // nine of the long one (down) take the same time within a microsecond; the larger counts are kept
+  // because an engine sized for 256 rows also runs steps of a few rows (a batch that is not refilled
+  // decays), and with few rows the bytes in flight, hence the weight bandwidth, grow with the slices.
+  if (M <= 256 && K <= 4096 && splits_valid(K, 4)) return 4;                    // 128 x 128 tiles
   return largest(((N + 127) / 128) * ((M + 255) / 256), 256);                   // 256 x 128 tiles
 }
 
@@ -381,12 +382,12 @@ int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, float *ws, int M, int
     else if (M <= 256 && N >= 128 * 256) { cfg = GEMM_128x256; paired = ks.splits == 1; }
     else cfg = GEMM_256x128;
   } else {
-    if (M <= 32) cfg = N >= 8192 ? GEMM_32x256 : GEMM_32x128;
-    else if (M <= 64) cfg = N >= 16384 ? GEMM_64x256 : GEMM_64x64;
+    if (M <= 32) cfg = N >= 16384 ? GEMM_32x256 : GEMM_32x128;   // all four wavefronts stream their own columns
+    else if (M <= 64 && N < 16384) cfg = GEMM_64x64;
+    else if (M <= 64) cfg = GEMM_64x256;
     else if (M <= 128) cfg = GEMM_128x256;
     else if (M <= 256 && ks.splits == 1 && N >= 128 * 256) { cfg = GEMM_128x256; paired = true; }
     else if (M <= 256 && K <= 4096) cfg = ks.splits <= 2 ? GEMM_128x64 : GEMM_128x128;
-    else if (M <= 256) cfg = GEMM_128x256;
     else cfg = GEMM_256x128;
   }
   int n_main = ks.n_main;
