@@ -509,15 +509,16 @@ int run_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) {
     HIP_TRY(hipStreamBeginCapture(w.stream, hipStreamCaptureModeThreadLocal));
     const int rc = enqueue_step(e, w, n, prefill);
     const hipError_t ce = hipStreamEndCapture(w.stream, &ng.graph);
-    if (rc || ce != hipSuccess) {
+    hipError_t ie = hipSuccess;
+    if (!rc && ce == hipSuccess) ie = hipGraphInstantiate(&ng.exec, ng.graph, nullptr, nullptr, 0);
+    if (rc || ce != hipSuccess || ie != hipSuccess) {
+      // Nothing was executed while capturing.  If the runtime cannot capture or instantiate this
+      // sequence, the engine goes on launching kernel by kernel (same results) for the rest of its life.
       drop_graph(ng);
       (void)hipGetLastError();
-      return rc ? rc : fail(PL_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
-    }
-    const hipError_t ie = hipGraphInstantiate(&ng.exec, ng.graph, nullptr, nullptr, 0);
-    if (ie != hipSuccess) {
-      drop_graph(ng);
-      return fail(PL_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(ie));
+      if (rc) return rc;
+      e->use_graphs = false;
+      return enqueue_step(e, w, n, prefill);
     }
     e->graphs.push_back(ng);
     g = &e->graphs.back();
