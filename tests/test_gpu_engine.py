@@ -696,3 +696,27 @@ def test_steps_replayed_from_a_graph_equal_steps_launched_kernel_by_kernel(weigh
         for x, y in zip(a, b):
             assert np.array_equal(x, y)
     assert len(shapes) >= 3       # the run did go through several launch shapes
+
+
+def test_more_launch_shapes_than_the_graph_cache_holds(weights):
+    """Row counts 1..40 in turn (more shapes than cached graphs, so the least recently used ones are dropped
+    and captured again later): every step equals the eager engine's, bit for bit."""
+    master, _ = weights
+    runs = []
+    for graphs in (False, True):
+        eng = _engine(max_batch=40, max_context=64, kv_pool_tokens=40 * 64)
+        eng.debug_set_graphs(graphs)
+        eng.load_weights(eng.pack_weights(master, synth.f32_to_bf16_bits))
+        rng = np.random.default_rng(71)
+        rec = []
+        for rnd in range(2):
+            for k in range(40):                     # grow the batch one sequence at a time
+                eng.add_sequence(1000 * rnd + k, rng.integers(0, M.vocab, 3), 60)
+                o = eng.decode_step()
+                rec.append((o["token"].copy(), o["logprob"].copy()))
+            for s in range(40):
+                eng.retire_sequence(s)
+        runs.append(rec)
+        eng.close()
+    for a, b in zip(*runs):
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])

@@ -215,3 +215,47 @@ def test_error_grows_like_the_root_of_the_depth():
         assert rel[b] >= 0.7 * rel[a], (a, b, rel)                            # noise does not vanish with depth
     for L in depths:
         assert rel[L] <= 1.3 * np.sqrt(L) * rel[1], (L, rel)
+
+
+def test_background_prompt_reading_at_full_size_while_the_batch_decodes(full):
+    """pl_prefill_async in the benchmark's configuration: the passes of one prompt run on their own stream
+    while all other slots keep decoding at full size (the two really overlap on the GPU here).  The cache
+    they leave must be bit-identical to the one blocking passes leave for the same prompt in a neighbouring
+    slot, and the decode steps that ran meanwhile must be unaffected: their log-probs are those of the
+    recorded logits, finite, and the batch keeps its other slots."""
+    eng, blob, m, spec, seed = full
+    n_prompt = spec["prompt"]
+    out = eng.decode_step()
+    victims = [int(s) for s in out["slot"][:2]]
+    for s in victims:
+        eng.retire_sequence(s)
+    prompt = synth.random_prompts(np.random.default_rng(43), 1, n_prompt, m.vocab)[0]
+    a = eng.add_sequence(920001, prompt, 2000)
+    assert eng.prefill(a) == n_prompt - 1                      # blocking
+    b = eng.add_sequence(920002, prompt, 2000)
+    assert eng.prefill_async(b) == n_prompt - 1                # in the background
+    joined = None
+    for step in range(40):
+        o = eng.decode_step()
+        assert np.isfinite(o["logprob"]).all()
+        if b in o["slot"].tolist():
+            joined = step
+            break
+        assert o["n"] == spec["batch"] - 1                     # everybody else keeps decoding meanwhile
+        for s in [int(s) for s, f in zip(o["slot"], o["finished"]) if f]:
+            eng.retire_sequence(s)
+            eng.add_sequence(930000 + s, prompt[:4], 2000)
+    assert joined is not None
+    print("the background reading took", joined, "decode steps")
+    for l in [0, m.n_layers // 2, m.n_layers - 1]:
+        ka, va = eng.debug_read_kv(a, l, n_prompt - 1)
+        kb, vb = eng.debug_read_kv(b, l, n_prompt - 1)
+        assert np.array_equal(ka, kb) and np.array_equal(va, vb), l
+        assert np.abs(ka).max() > 0
+    # both copies of the sequence now produce the same logits at the same position
+    for _ in range(2):
+        o = eng.decode_step()
+        rows = {int(s): i for i, s in enumerate(o["slot"])}
+        lg = eng.debug_get_logits(o["n"])
+        if o["position"][rows[a]] == o["position"][rows[b]]:
+            assert np.array_equal(lg[rows[a]], lg[rows[b]])
