@@ -73,6 +73,10 @@ typedef struct {
                              has the same tensors in the same order, 4 bytes per element, every matrix
                              row-major [out, in], "l<l>.w_gu" = all gate rows then all up rows
                              (pl_pack_weights produces it).  Same calls, same semantics; slow. */
+  int32_t tie_embeddings; /* 0: untied LM head (default).  1: the LM head is the embedding table: the blob
+                             ends after "gf" (pl_weight_count / pl_weight_layout / pl_weight_nbytes do not
+                             list an lm_head), and every load or update derives the LM head's streaming
+                             layout from the table on the device, behind the copy that brought the blob in */
 } pl_model_cfg;
 
 /* Result of one decode step: one entry per occupied slot, in slot order.  Arrays are caller

@@ -39,7 +39,7 @@ class ModelCfg(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("max_batch", C.c_int32),
                 ("max_context", C.c_int32), ("kv_pool_tokens", C.c_int64), ("kv_page_tokens", C.c_int32),
-                ("n_weight_buffers", C.c_int32), ("seed", C.c_uint64), ("device", C.c_int32), ("dtype", C.c_int32)]
+                ("n_weight_buffers", C.c_int32), ("seed", C.c_uint64), ("device", C.c_int32), ("dtype", C.c_int32), ("tie_embeddings", C.c_int32)]
 
 
 class StepOut(C.Structure):
@@ -148,10 +148,10 @@ class Engine:
 
     def __init__(self, *, n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, max_batch,
                  max_context, kv_pool_tokens, rope_theta=1.0e4, rms_eps=1.0e-6, kv_page_tokens=0,
-                 n_weight_buffers=2, seed=0, device=0, dtype=PL_BF16):
+                 n_weight_buffers=2, seed=0, device=0, dtype=PL_BF16, tie_embeddings=0):
         self.cfg = ModelCfg(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab, rope_theta,
                             rms_eps, max_batch, max_context, kv_pool_tokens, kv_page_tokens, n_weight_buffers,
-                            seed, device, dtype)
+                            seed, device, dtype, tie_embeddings)
         self._h = C.c_void_p()
         _check(lib().pl_create(C.byref(self.cfg), C.byref(self._h)))
         B = max_batch
@@ -224,6 +224,8 @@ class Engine:
         f32 = self.cfg.dtype == PL_F32
         blob = np.zeros(self.weight_nbytes() // (4 if f32 else 2), np.float32 if f32 else np.uint16)
         for name, w in tensors.items():
+            if name == "lm_head" and self.cfg.tie_embeddings:
+                continue
             w = np.ascontiguousarray(w, np.float32)
             _check(lib().pl_pack_weights(self._h, name.encode(), _np_ptr(w), 1, _np_ptr(blob)))
         return blob

@@ -180,6 +180,17 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restric
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u && sink) sink[0] = 1;   // keeps the loads alive
 }
 
+// LM head tied to the embedding table: dst = the [vocab, d] row-major table in the layout the LM-head
+// GEMM streams (bf16: MFMA operand order, 16-byte pieces of 8 consecutive columns; fp32 build: a plain copy).
+__global__ void tie_lm_head_kernel(const bf16x8 *__restrict__ embed, bf16x8 *__restrict__ dst, int vocab, int d) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 8-column piece
+  const int d8 = d >> 3;
+  if (idx >= (int64_t)vocab * d8) return;
+  const int r = (int)(idx / d8), c = (int)(idx % d8) * 8;
+  const int64_t o = ((int64_t)(c / 64) * (vocab / 32) + r / 32) * 2048 + ((c % 32) / 8) * 512 + ((c % 64) / 32) * 256 + (r % 32) * 8;
+  dst[o >> 3] = embed[idx];
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, uint32_t v, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -238,6 +249,14 @@ int64_t launch_stream_read(const void *p, int64_t nbytes, uint32_t *sink, bool n
   else
     hipLaunchKernelGGL(stream_read_kernel<false>, dim3(wgs), dim3(256), 0, s, (const u32x4 *)p, sink, n_per_wg);
   return hipGetLastError() == hipSuccess ? n_per_wg * 16 * wgs : -7;
+}
+
+int launch_tie_lm_head(const void *embed, void *lm_head, int vocab, int d, bool f32, hipStream_t s) {
+  if (f32) return hipMemcpyAsync(lm_head, embed, (size_t)vocab * d * 4, hipMemcpyDeviceToDevice, s) == hipSuccess ? 0 : -7;
+  const int64_t pieces = (int64_t)vocab * (d / 8);
+  hipLaunchKernelGGL(tie_lm_head_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, s, (const bf16x8 *)embed,
+                     (bf16x8 *)lm_head, vocab, d);
+  return ok();
 }
 
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s) {

@@ -106,6 +106,7 @@ int f32_launch_attention(const float *q, const float *kv_layer, const int32_t *p
                          int pages_per_seq, hipStream_t s);
 int64_t launch_stream_read(const void *p, int64_t nbytes, uint32_t *sink, bool nontemporal, hipStream_t s);
 int launch_fill_u32(uint32_t *p, uint32_t v, int64_t n, hipStream_t s);
+int launch_tie_lm_head(const void *embed, void *lm_head, int vocab, int d, bool f32, hipStream_t s);
 int launch_is_ess(const float *lp_pi, const float *lp_mu, const int64_t *offsets, int n_seq, double c, float *w_out,
                   double *seq_sums, double *ess_seq, double *totals, hipStream_t s);
 

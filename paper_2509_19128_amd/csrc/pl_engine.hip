@@ -79,7 +79,9 @@ struct pl_engine {
   int64_t n_pages = 0, layer_stride = 0, page_stride = 0;   // elements
   // weights
   std::vector<Tensor> layout;
-  int64_t blob_elems = 0;
+  int64_t blob_elems = 0;        // elements of a device weight buffer (always with an LM head)
+  int64_t host_blob_elems = 0;   // elements of the caller's blob: without the LM head when it is tied to the embedding
+  bool tied = false;
   bool f32 = false;   // the fp32 test build
   int esz = 2;        // bytes per stored element (weights, KV, activations)
   char *wbuf[2] = {nullptr, nullptr};
@@ -190,6 +192,7 @@ void build_layout(pl_engine *e) {
   add("gf", d, 1);
   add("lm_head", c.vocab, d);
   e->blob_elems = off;
+  e->host_blob_elems = e->tied ? off - (int64_t)c.vocab * d : off;
   e->streamed_weight_bytes = (int64_t)e->esz * (off - (int64_t)c.vocab * d);
 }
 
@@ -528,6 +531,18 @@ int run_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) {
   return PL_OK;
 }
 
+// Tied embeddings: the LM head of weight buffer `buf` is the embedding table, stored once more in the
+// layout the LM-head GEMM streams.  Enqueued behind the copy that brought the blob in.
+int tie_lm_head(pl_engine *e, int buf, hipStream_t s) {
+  if (!e->tied) return PL_OK;
+  const pl_model_cfg &c = e->cfg;
+  char *base = e->wbuf[buf];
+  const int64_t eo = e->layout.front().offset, lo = e->layout.back().offset;
+  if (pl::launch_tie_lm_head(base + eo * e->esz, base + lo * e->esz, c.vocab, c.d_model, e->f32, s))
+    return fail(PL_E_HIP, "LM-head tie launch failed");
+  return PL_OK;
+}
+
 void activate_staged(pl_engine *e) {
   if (e->cfg.n_weight_buffers == 2) e->active_buf ^= 1;
   e->version = e->staged_version;
@@ -705,6 +720,7 @@ int pl_create(const pl_model_cfg *cfg, pl_engine **out) {
   e->dry = cfg->device == PL_DEVICE_NONE;
   e->f32 = cfg->dtype == PL_F32;
   e->esz = e->f32 ? 4 : 2;
+  e->tied = cfg->tie_embeddings != 0;
   e->G = cfg->n_q_heads / cfg->n_kv_heads;
   e->page_tokens = cfg->kv_page_tokens ? cfg->kv_page_tokens : 128;
   e->pages_per_seq = (cfg->max_context + e->page_tokens - 1) / e->page_tokens;
@@ -775,10 +791,11 @@ void pl_destroy(pl_engine *e) {
   delete e;
 }
 
-int32_t pl_weight_count(const pl_engine *e) { return e ? (int32_t)e->layout.size() : 0; }
+// the caller's blob ends before the LM head when that is tied to the embedding table
+int32_t pl_weight_count(const pl_engine *e) { return e ? (int32_t)e->layout.size() - (e->tied ? 1 : 0) : 0; }
 
 int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t *offset_elems, int64_t shape[2]) {
-  if (!e || idx < 0 || idx >= (int32_t)e->layout.size()) return fail(PL_E_INVAL, "tensor index out of range");
+  if (!e || idx < 0 || idx >= pl_weight_count(e)) return fail(PL_E_INVAL, "tensor index out of range");
   const Tensor &t = e->layout[idx];
   if (name) *name = t.name.c_str();
   if (offset_elems) *offset_elems = t.offset;
@@ -786,7 +803,7 @@ int pl_weight_layout(const pl_engine *e, int32_t idx, const char **name, int64_t
   return PL_OK;
 }
 
-int64_t pl_weight_nbytes(const pl_engine *e) { return e ? e->blob_elems * e->esz : 0; }
+int64_t pl_weight_nbytes(const pl_engine *e) { return e ? e->host_blob_elems * e->esz : 0; }
 
 int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32_t src_is_f32, void *blob) {
   if (!e || !name || !src || !blob) return fail(PL_E_INVAL, "NULL argument");
@@ -816,6 +833,7 @@ int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32
   for (const Tensor &x : e->layout)
     if (x.name == target) { t = &x; break; }
   if (!t) return fail(PL_E_INVAL, "unknown tensor '%s'", name);
+  if (e->tied && t->name == "lm_head") return fail(PL_E_INVAL, "the LM head is tied to the embedding table; the blob holds no lm_head");
   if (e->f32) {   // test build: fp32, row-major, rows placed at row0 (gate rows first, then up rows)
     if (!src_is_f32) return fail(PL_E_INVAL, "the fp32 build packs fp32 sources");
     if (interleave == 1) row0 = c.d_ffn;
@@ -843,13 +861,16 @@ int pl_pack_weights(const pl_engine *e, const char *name, const void *src, int32
 
 int pl_load_weights(pl_engine *e, const void *src, int64_t nbytes) {
   if (!e || !src) return fail(PL_E_INVAL, "NULL argument");
-  if (nbytes != e->blob_elems * e->esz) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * e->esz));
+  if (nbytes != e->host_blob_elems * e->esz) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->host_blob_elems * e->esz));
   if (e->staged) return fail(PL_E_BUSY, "a weight update is staged");
   if (!e->dry) {
     HIP_TRY(hipSetDevice(e->cfg.device));
     HIP_TRY(hipStreamSynchronize(e->s_dec));
     HIP_TRY(hipStreamSynchronize(e->wk[1].stream));   // a prompt read in the background finishes under the old weights
     HIP_TRY(hipMemcpy(e->wbuf[e->active_buf], src, (size_t)nbytes, hipMemcpyDefault));
+    int rc = tie_lm_head(e, e->active_buf, e->s_dec);
+    if (rc) return rc;
+    HIP_TRY(hipStreamSynchronize(e->s_dec));
   }
   if (e->loaded) { e->version++; e->st.swaps++; }
   e->loaded = true;
@@ -862,7 +883,7 @@ int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flag
   if (flags & PL_SWAP_RECOMPUTE_KV)
     for (const Seq &q : e->seqs)
       if (q.active && !q.hist_known) return fail(PL_E_STATE, "a sequence was admitted without its token history; its cache cannot be recomputed");
-  if (nbytes != e->blob_elems * e->esz) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->blob_elems * e->esz));
+  if (nbytes != e->host_blob_elems * e->esz) return fail(PL_E_INVAL, "weight blob is %lld bytes, expected %lld", (long long)nbytes, (long long)(e->host_blob_elems * e->esz));
   if (!e->loaded) return fail(PL_E_STATE, "no weights loaded yet");
   if (e->staged) return fail(PL_E_BUSY, "the previous weight update is not active yet");
   e->staged_version = e->version + 1;
@@ -876,11 +897,15 @@ int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flag
       if (e->pre_pending) HIP_TRY(hipStreamWaitEvent(e->s_copy, e->ev_pre_last, 0));
       HIP_TRY(hipEventRecord(e->ev_copy0, e->s_copy));
       HIP_TRY(hipMemcpyAsync(e->wbuf[e->active_buf ^ 1], src, (size_t)nbytes, hipMemcpyDefault, e->s_copy));
+      int rc = tie_lm_head(e, e->active_buf ^ 1, e->s_copy);
+      if (rc) return rc;
       HIP_TRY(hipEventRecord(e->ev_staged, e->s_copy));
     } else {
       HIP_TRY(hipStreamSynchronize(e->wk[1].stream));
       HIP_TRY(hipEventRecord(e->ev_copy0, e->s_dec));
       HIP_TRY(hipMemcpyAsync(e->wbuf[0], src, (size_t)nbytes, hipMemcpyDefault, e->s_dec));
+      int rc = tie_lm_head(e, 0, e->s_dec);
+      if (rc) return rc;
       HIP_TRY(hipEventRecord(e->ev_staged, e->s_dec));
       HIP_TRY(hipStreamSynchronize(e->s_dec));
       e->staged_wait = true;

@@ -353,3 +353,19 @@ def test_fp32_test_build_blob_is_row_major_fp32():
     with pytest.raises(pl.PlError) as ex:
         _engine(dtype=7)
     assert ex.value.code == pl.PL_E_INVAL
+
+
+def test_tied_embeddings_blob_has_no_lm_head():
+    e = _engine(tie_embeddings=1)
+    names = [n for n, _, _ in e.weight_layout()]
+    assert names[0] == "embed" and names[-1] == "gf" and "lm_head" not in names
+    assert e.weight_nbytes() == 2 * M.streamed_params()          # embedding table in, LM head out: same count
+    W = synth.make_weights(M, 17)
+    blob = e.pack_weights(W, synth.f32_to_bf16_bits)
+    assert blob.size * 2 == e.weight_nbytes()
+    assert np.array_equal(e.pack_weights_c(W), blob)
+    L = pl.lib()
+    assert L.pl_pack_weights(e._h, b"lm_head", blob.ctypes.data, 0, blob.ctypes.data) == pl.PL_E_INVAL
+    e.load_weights(blob)
+    e.add_sequence(1, [1, 2], 2)
+    assert e.decode_step()["n"] == 1

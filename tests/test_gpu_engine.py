@@ -720,3 +720,42 @@ def test_more_launch_shapes_than_the_graph_cache_holds(weights):
         eng.close()
     for a, b in zip(*runs):
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_tied_embeddings_against_the_oracle_with_an_update(weights, dtype):
+    """tie_embeddings = 1: the blob carries no LM head; the engine derives it from the embedding table at
+    every load and update.  Oracle: the same decoder with lm_head = embed."""
+    master, pert = weights
+    f32 = dtype == "f32"
+    tied = [dict(w, lm_head=w["embed"]) for w in (master, pert)]
+    eng = _engine(tie_embeddings=1, dtype=pl.PL_F32 if f32 else pl.PL_BF16)
+    blobs = [eng.pack_weights({k: v for k, v in w.items() if k != "lm_head"}, synth.f32_to_bf16_bits) for w in tied]
+    assert blobs[0].nbytes == eng.weight_nbytes()
+    eng.load_weights(blobs[0])
+    prep = (lambda w: {k: v.astype(np.float64) for k, v in w.items()}) if f32 else _rounded
+    orc = OracleEngine(M, prep(tied[0]), max_batch=4, seed=SEED)
+    prompts = synth.random_prompts(np.random.default_rng(81), 4, 6, M.vocab)
+    for i in range(4):
+        eng.add_sequence(i, prompts[i], 20); orc.add_sequence(i, prompts[i], 20)
+    atol, rtol = (1e-4, 1e-4) if f32 else (ATOL, RTOL)
+    for step in range(22):
+        if step == 9:
+            orc.swap_weights(prep(tied[1]))
+            eng.swap_weights(blobs[1], flags=pl.PL_SWAP_WAIT)
+        if step == 15:
+            orc.swap_weights(prep(tied[0]))
+            eng.swap_weights(blobs[0], flags=pl.PL_SWAP_ASYNC)
+            while not eng.swap_poll()[0]:
+                pass
+        recs = orc.decode_step()
+        forced = np.full(4, -1, np.int32)
+        for r in recs:
+            forced[r.slot] = r.token
+        out = eng.decode_step(forced)
+        lg = eng.debug_get_logits(out["n"])
+        for i, r in enumerate(recs):
+            assert out["weight_version"][i] == r.weight_version
+            ok, err = close(lg[i], orc.last_logits[r.slot], atol, rtol)
+            assert ok, (step, i, err)
+    eng.close()
