@@ -172,7 +172,40 @@ static void bad_configurations(void) {
   pl_destroy(NULL);
 }
 
+static void build_variants(void) {
+  /* fp32 test build and tied embeddings: blob sizes, layout enumeration, packing */
+  for (int variant = 0; variant < 4; ++variant) {
+    pl_model_cfg c = tiny(3, 64, 0, 32);
+    c.dtype = variant & 1 ? PL_F32 : PL_BF16;
+    c.tie_embeddings = variant >> 1;
+    pl_engine *e = NULL;
+    CHECK(pl_create(&c, &e) == PL_OK);
+    const int64_t nbytes = pl_weight_nbytes(e), esz = c.dtype == PL_F32 ? 4 : 2;
+    int64_t elems = 0;
+    for (int32_t i = 0; i < pl_weight_count(e); ++i) {
+      const char *name; int64_t off, shp[2];
+      CHECK(pl_weight_layout(e, i, &name, &off, shp) == PL_OK && off == elems);
+      elems += shp[0] * shp[1];
+      CHECK(!(c.tie_embeddings && strcmp(name, "lm_head") == 0));
+    }
+    CHECK(elems * esz == nbytes);
+    char *blob = calloc(nbytes, 1);
+    float *src = malloc(4096 * 256 * 4);
+    for (int i = 0; i < 4096 * 256; ++i) src[i] = (float)(i % 97) * 0.01f;
+    CHECK(pl_pack_weights(e, "embed", src, 1, blob) == PL_OK);
+    CHECK(pl_pack_weights(e, "l1.wu", src, 1, blob) == PL_OK);
+    CHECK(pl_pack_weights(e, "l0.wk", src, 1, blob) == PL_OK);
+    CHECK(pl_pack_weights(e, "lm_head", src, 1, blob) == (c.tie_embeddings ? PL_E_INVAL : PL_OK));
+    if (c.dtype == PL_F32) CHECK(pl_pack_weights(e, "l0.wq", src, 0, blob) == PL_E_INVAL);   /* fp32 sources only */
+    CHECK(pl_load_weights(e, blob, nbytes) == PL_OK);
+    free(src);
+    free(blob);
+    pl_destroy(e);
+  }
+}
+
 int main(void) {
+  build_variants();
   const int32_t batches[] = {1, 3, 4, 64, 257, 511};
   for (unsigned i = 0; i < sizeof batches / sizeof *batches; ++i) life_cycle(batches[i]);
   pool_exhaustion();
