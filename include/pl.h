@@ -206,7 +206,8 @@ int pl_add_sequence(pl_engine *e, uint64_t seq_id, const int32_t *prompt, int32_
  * identical arithmetic: same kernels, same per-row operation order) and emits nothing; the next
  * pl_decode_step reads the last prompt token and produces the first generated token.
  * *out_positions (may be NULL) receives the number of positions read (0 if none were left).
- * Blocks until done.  PL_E_STATE if the slot is idle or before pl_load_weights. */
+ * Blocks until done (on a slot that pl_prefill_async is already reading: until that reading is done).
+ * PL_E_STATE if the slot is idle or before pl_load_weights. */
 int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions);
 /* The same reading, in the background: the passes are enqueued on a stream of their own and the call
  * returns at once, so decode steps of the other slots go on meanwhile (the passes are GEMM-bound, the

@@ -1218,7 +1218,10 @@ static int start_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
 
 int pl_prefill(pl_engine *e, int32_t slot, int32_t *out_positions) {
   if (!e) return fail(PL_E_INVAL, "NULL argument");
-  int rc = start_prefill(e, slot, out_positions);
+  // a slot whose prompt is already being read in the background: nothing is left to read, wait for it
+  const bool already = slot >= 0 && slot < e->cfg.max_batch && e->seqs[slot].active && e->seqs[slot].reading;
+  if (already && out_positions) *out_positions = 0;
+  int rc = already ? PL_OK : start_prefill(e, slot, out_positions);
   if (rc) return rc;
   Seq &q = e->seqs[slot];
   if (q.reading) {

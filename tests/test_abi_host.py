@@ -332,6 +332,10 @@ def test_background_prompt_reading_bookkeeping():
     e.retire_sequence(s2)                     # retiring a slot that is still reading is allowed
     assert e.num_active() == 2
     assert e.prefill_async(s1) == 0           # nothing left to read
+    s3 = e.add_sequence(4, list(range(30, 40)), 2)
+    assert e.prefill_async(s3) == 9 and e.prefill(s3) == 0      # the blocking call waits for the reading under way
+    r = e.decode_step()
+    assert s3 in r["slot"].tolist()
 
 
 def test_fp32_test_build_blob_is_row_major_fp32():
