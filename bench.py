@@ -738,12 +738,13 @@ def main():
     med = float(np.median(sm))
     # swap stall: the step that contains the flip against the median of the 16 surrounding steps (None if no
     # flip fell inside the timed window: nothing was measured then)
-    stall_ms = None
+    stall_ms, stall_each = None, []
     for k in flips:
         lo, hi = max(0, k - 8), min(len(sm), k + 9)
         around = np.concatenate([sm[lo:k], sm[k + 1:hi]])
         if len(around):
-            stall_ms = max(stall_ms or 0.0, float(sm[k] - np.median(around)) + float(stalls[k]))
+            stall_each.append(float(sm[k] - np.median(around)) + float(stalls[k]))
+            stall_ms = max(stall_ms or 0.0, stall_each[-1])
     # interference: decode steps that run while a staging copy is in flight (request .. flip) against the rest
     during = np.zeros(len(sm), bool)
     for rq in requests:
@@ -773,6 +774,9 @@ def main():
                      "frac_of_8TBs": d["algorithmic_bytes"] / max(d["gpu_ms_total"], 1e-9) / 1e6 / HBM_PEAK_GBS},
         "swap": {"requested": swaps_requested, "requested_at_steps": requests, "flips_at_steps": flips,
                  "window_contains_a_flip": bool(flips), "stall_ms": stall_ms,
+                 # per flip; a flip step that also shares the GPU with a background prompt-reading pass shows that
+                 # pass's slowdown here (a few ms), not a wait for the update
+                 "stall_ms_per_flip": stall_each,
                  "steps_overlapping_a_copy": int(during.sum()), "interference_ms_per_overlapping_step": interference,
                  "copy_ms": s1["last_swap_copy_ms"], "blob_GB": eng.weight_nbytes() / 1e9,
                  "kv_cache": "recomputed at the flip" if args.recompute_kv else "kept",
