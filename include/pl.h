@@ -281,6 +281,19 @@ int pl_debug_kv_pool(pl_engine *e, void **device_ptr, int64_t *nbytes);
 int pl_debug_gemm_cfg(int32_t cfg, const void *x, const void *w, void *y, void *ws, int32_t M, int32_t N, int32_t K,
                       int32_t mode, int32_t splits, int32_t n_begin, int32_t n_end, int32_t paired, void *stream);
 
+/* The K split an engine of max_batch = M_max fixes for the product [*, K] x [N, K]^T (mode as in
+ * pl_gemm_bf16): columns [0, n_main) in `splits` slices, columns [n_main, N) in `rem_splits` (mode 0:
+ * n_main = N), and the fp32 elements of workspace a mode-1 product then needs (0: none).  Any output
+ * pointer may be NULL. */
+int pl_debug_gemm_plan(int32_t M_max, int32_t N, int32_t K, int32_t mode, int32_t *splits, int32_t *n_main,
+                       int32_t *rem_splits, int64_t *ws_elems);
+/* The product of M <= M_max rows launched exactly as such an engine launches it for a pass of M rows
+ * (tile shapes from M, K split from M_max).  mode 0: y is device fp32 [splits, M, N]; mode 1: y is device
+ * bf16 [M, N / 2], ws device fp32 of ws_elems (may be NULL when that is 0).  Outputs of the same x rows
+ * are bit-identical for every M <= M_max.  PL_E_INVAL (nothing launched) for unsupported shapes. */
+int pl_debug_gemm_planned(const void *x, const void *w, void *y, void *ws, int32_t M_max, int32_t M, int32_t N, int32_t K,
+                          int32_t mode, void *stream);
+
 /* Launch a kernel that only reads the device buffer (contiguous 16-byte loads, 8 in flight per lane;
  * ordinary loads, or non-temporal ones if `nontemporal` is non-zero) on `stream`; returns the number of bytes it reads (a multiple of 256 MiB, <= nbytes) or a negative
  * pl_status.  Timed by the caller, it gives the read bandwidth HBM delivers on this board. */

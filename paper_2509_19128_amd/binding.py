@@ -10,7 +10,7 @@ __all__ = [
     "PL_OK", "PL_E_INVAL", "PL_E_NOSLOT", "PL_E_NOKV", "PL_E_BUSY", "PL_E_STATE", "PL_E_CTX", "PL_E_HIP",
     "PL_E_NOMEM", "PL_SWAP_ASYNC", "PL_SWAP_WAIT", "PL_SWAP_RECOMPUTE_KV", "PL_DEVICE_NONE", "PL_BF16", "PL_F32", "PlError", "ModelCfg", "StepOut", "Stats",
     "lib", "library_path", "Engine", "operand_order", "pl_attention_decode", "pl_attention_workspace_bytes", "pl_kv_pack_host",
-    "pl_gemm_bf16", "pl_debug_gemm_cfg", "pl_sample", "pl_sample_static", "pl_sample_workspace_bytes", "pl_debug_stream_read", "pl_is_ess", "EXPORTS",
+    "pl_gemm_bf16", "pl_debug_gemm_cfg", "pl_debug_gemm_plan", "pl_debug_gemm_planned", "pl_sample", "pl_sample_static", "pl_sample_workspace_bytes", "pl_debug_stream_read", "pl_is_ess", "EXPORTS",
 ]
 
 PL_OK, PL_E_INVAL, PL_E_NOSLOT, PL_E_NOKV, PL_E_BUSY, PL_E_STATE, PL_E_CTX, PL_E_HIP, PL_E_NOMEM = 0, -1, -2, -3, -4, -5, -6, -7, -8
@@ -23,7 +23,7 @@ EXPORTS = [
     "pl_create", "pl_destroy", "pl_last_error", "pl_weight_count", "pl_weight_layout", "pl_weight_nbytes",
     "pl_pack_weights", "pl_load_weights", "pl_swap_weights", "pl_swap_poll", "pl_add_sequence", "pl_prefill", "pl_prefill_async", "pl_retire_sequence",
     "pl_num_active", "pl_decode_step", "pl_get_stats", "pl_debug_get_logits", "pl_debug_read_kv",
-    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_set_graphs", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_gemm_cfg", "pl_debug_stream_read", "pl_attention_workspace_bytes",
+    "pl_debug_write_kv", "pl_debug_add_sequence_at", "pl_debug_set_history", "pl_debug_set_poison", "pl_debug_set_graphs", "pl_debug_kv_pool", "pl_debug_set_profile", "pl_debug_gemm_cfg", "pl_debug_gemm_plan", "pl_debug_gemm_planned", "pl_debug_stream_read", "pl_attention_workspace_bytes",
     "pl_attention_decode", "pl_kv_pack_host", "pl_gemm_bf16", "pl_sample_workspace_bytes", "pl_sample", "pl_sample_static", "pl_is_ess",
 ]
 
@@ -111,6 +111,8 @@ def lib():
         "pl_debug_set_graphs": (C.c_int, [vp, i32]),
         "pl_debug_stream_read": (i64, [vp, i64, i32, vp]),
         "pl_debug_gemm_cfg": (C.c_int, [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]),
+        "pl_debug_gemm_plan": (C.c_int, [i32, i32, i32, i32, vp, vp, vp, vp]),
+        "pl_debug_gemm_planned": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
         "pl_attention_workspace_bytes": (i64, [i32, i32, i32, i32, i32]),
         "pl_attention_decode": (C.c_int, [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp]),
         "pl_kv_pack_host": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32]),
@@ -396,6 +398,17 @@ def pl_gemm_bf16(x, w, y, M, N, K, mode=0, splits=1, stream=0):
 
 def pl_debug_gemm_cfg(cfg, x, w, y, ws, M, N, K, mode, splits, n_begin, n_end, paired=False, stream=0):
     _check(lib().pl_debug_gemm_cfg(cfg, x, w, y, ws, M, N, K, mode, splits, n_begin, n_end, int(bool(paired)), stream))
+
+
+def pl_debug_gemm_plan(M_max, N, K, mode):
+    """(splits, n_main, rem_splits, ws_elems) an engine of max_batch = M_max fixes for this product."""
+    sp, nm, rs, ws = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int64()
+    _check(lib().pl_debug_gemm_plan(M_max, N, K, mode, C.byref(sp), C.byref(nm), C.byref(rs), C.byref(ws)))
+    return sp.value, nm.value, rs.value, ws.value
+
+
+def pl_debug_gemm_planned(x, w, y, ws, M_max, M, N, K, mode, stream=0):
+    _check(lib().pl_debug_gemm_planned(x, w, y, ws, M_max, M, N, K, mode, stream))
 
 
 def pl_sample_workspace_bytes(n, vocab):

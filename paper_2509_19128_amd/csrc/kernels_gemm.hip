@@ -24,31 +24,20 @@ constexpr int LDS_ROW = 72;     // padded row length (elements) of the x tile in
 // tile runs two k-steps ahead through a 2-deep register stage and a double-buffered LDS tile.
 // Within a k-step the x loads are issued before the W loads, so waiting for an x tile (in-order
 // completion) never waits for the younger W loads.
+//
+// gemm_tile computes one tile (column tile at n_tile0, rows from m0, K slice `split`) with the whole
+// workgroup; the kernels below are thin wrappers that pick the tile(s) of a workgroup.
 template <int WM, int WN, int AT, int BT, int MODE>
-__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
-                                                   void *__restrict__ Yv, int M, int N, int K, int ksteps,
-                                                   int n_base, int n_end, int nrow, int ldy, int y_col0) {
-  constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
+__device__ __forceinline__ void gemm_tile(bf16_t (*xs)[WM * AT * 32 * LDS_ROW], const bf16_t *__restrict__ X,
+                                          const bf16_t *__restrict__ W, void *__restrict__ Yv, int M, int N, int K,
+                                          int ksteps, int n_tile0, int m0, int split, int n_end, int ldy, int y_col0) {
+  constexpr int BM = WM * AT * 32;
   constexpr int XCH = BM * (BK / 8) / 256;       // 16-byte chunks of the x tile per thread
   static_assert(WM * WN == 4 && XCH >= 1, "tile");
-  __shared__ __attribute__((aligned(16))) bf16_t xs[2][BM * LDS_ROW];
-
   const int tid = threadIdx.x, l = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps W offsets in scalar registers
   const int wm = wave / WN, wn = wave % WN;
-  // Tile of this workgroup.  nrow = 0: (column tile, row tile) = (blockIdx.x, blockIdx.z).  nrow > 0:
-  // a flat grid in which the row tiles of one column tile sit 8 workgroup ids apart, so the hardware's
-  // round-robin deal of consecutive ids to the 8 XCDs puts them on the same XCD at the same moment
-  // and the second reader of a W tile finds it in that XCD's L2.
-  int ctile = blockIdx.x, rtile = blockIdx.z;
-  if (nrow > 0) {
-    rtile = (blockIdx.x >> 3) % nrow;
-    ctile = (blockIdx.x / (8 * nrow)) * 8 + (blockIdx.x & 7);
-    if (n_base + ctile * BN >= n_end) return;   // padding of the flat grid (uniform for the workgroup)
-  }
-  const int n0 = n_base + ctile * BN + wn * BT * 32;
-  const int m0 = rtile * BM;
-  const int split = blockIdx.y;
+  const int n0 = n_tile0 + wn * BT * 32;
   const int kbeg = split * ksteps * BK;
   const int nks = min(ksteps, K / BK - split * ksteps);
   const int lrow = l & 31, half = l >> 5;
@@ -215,6 +204,52 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
   }
 }
 
+template <int WM, int WN, int AT, int BT, int MODE>
+__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
+                                                   void *__restrict__ Yv, int M, int N, int K, int ksteps,
+                                                   int n_base, int n_end, int nrow, int ldy, int y_col0) {
+  constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][BM * LDS_ROW];
+  // Tile of this workgroup.  nrow = 0: (column tile, row tile) = (blockIdx.x, blockIdx.z).  nrow > 0:
+  // a flat grid in which the row tiles of one column tile sit 8 workgroup ids apart, so the hardware's
+  // round-robin deal of consecutive ids to the 8 XCDs puts them on the same XCD at the same moment
+  // and the second reader of a W tile finds it in that XCD's L2.
+  int ctile = blockIdx.x, rtile = blockIdx.z;
+  if (nrow > 0) {
+    rtile = (blockIdx.x >> 3) % nrow;
+    ctile = (blockIdx.x / (8 * nrow)) * 8 + (blockIdx.x & 7);
+    if (n_base + ctile * BN >= n_end) return;   // padding of the flat grid (uniform for the workgroup)
+  }
+  gemm_tile<WM, WN, AT, BT, MODE>(xs, X, W, Yv, M, N, K, ksteps, n_base + ctile * BN, rtile * BM, blockIdx.y, n_end, ldy, y_col0);
+}
+
+// The SwiGLU product of a 129..256-row batch in ONE launch of one workgroup per compute unit.  Phase 1:
+// workgroup i computes main tile i (128 x 256, row tiles paired on an XCD as above) with the SwiGLU
+// epilogue.  Phase 2: the columns left over beyond the last full round of tiles, [n_main, N), are cut
+// into 128 x 256 tiles and those along K into `rem_splits` slices; workgroup i takes slice i % rem_splits
+// of tile i / rem_splits and writes its fp32 partial sums to ws, as a launch of the plain kernel with that
+// K split would (same slices, same k order); swiglu_reduce_kernel finishes them.  Every unit thus works
+// 56 + 12 k-steps at the 7B shape instead of 256 units 56 and then 160 units 56 more on quarter-size tiles.
+template <int WM, int WN, int AT, int BT>
+__global__ __launch_bounds__(256) void gemm_gu_fused_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
+                                                            bf16_t *__restrict__ mid, float *__restrict__ ws, int M, int N,
+                                                            int K, int n_main, int rem_splits, int rem_ksteps) {
+  constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
+  __shared__ __attribute__((aligned(16))) bf16_t xs[2][BM * LDS_ROW];
+  const int nrow = (M + BM - 1) / BM;
+  {
+    const int rtile = (blockIdx.x >> 3) % nrow, ctile = (blockIdx.x / (8 * nrow)) * 8 + (blockIdx.x & 7);
+    if (ctile * BN < n_main)
+      gemm_tile<WM, WN, AT, BT, 1>(xs, X, W, mid, M, N, K, K / BK, ctile * BN, rtile * BM, 0, n_main, 0, 0);
+  }
+  const int item = blockIdx.x / rem_splits, split = blockIdx.x % rem_splits;
+  const int rem_ctiles = (N - n_main + BN - 1) / BN;
+  if (item >= rem_ctiles * nrow) return;
+  __syncthreads();   // the x tile of phase 1 is dead only when every wavefront has left its last k-step
+  const int ctile = item / nrow, rtile = item % nrow;
+  gemm_tile<WM, WN, AT, BT, 0>(xs, X, W, ws, M, N, K, rem_ksteps, n_main + ctile * BN, rtile * BM, split, N, N - n_main, n_main);
+}
+
 // SwiGLU over K-split partial sums: parts [splits][M][ld] holds columns [col0, col0 + ld) of the
 // interleaved gate/up product (blocks of 64 columns: 32 gate, then the 32 matching up columns);
 // mid[m][(col0 + c) / 2 ...] = silu(sum_s gate) * (sum_s up), slices added in order.
@@ -349,11 +384,29 @@ int gemm_pick_splits(int M, int N, int K) {
 // mode 0: one split count for all columns (the caller's output holds that many slices).
 // mode 1: columns [0, n_main) with `splits` slices, columns [n_main, N) with `rem_splits`; wherever a
 // count exceeds 1 the partial sums go through the workspace and the SwiGLU is applied by a reduction.
-// In the sweeps no SwiGLU product gained from a K split (64 x 128 tiles fill the chip for narrow
-// batches, and the column remainder of the wide ones is bound by its fixed costs), so none is chosen.
+// Launched on their own, no SwiGLU product gained from a K split in the sweeps (64 x 128 tiles fill the
+// chip for narrow batches).  The one split chosen is the column remainder of a wide product at 129..256
+// rows, whose slices ride in the launch of the main tiles (gemm_gu_fused_kernel): 1.2 % of the 7B step.
 GemmSplit gemm_pick_split(int M_max, int N, int K, int mode) {
   GemmSplit ks{1, N, 1};
-  if (mode == 0) ks.splits = gemm_pick_splits(M_max, N, K);
+  if (mode == 0) {
+    ks.splits = gemm_pick_splits(M_max, N, K);
+    return ks;
+  }
+  if (M_max > 128 && M_max <= 256 && N >= 128 * 256) {
+    // 128 x 256 tiles, two row tiles: what is left over a multiple of 256 tiles is split along K so that
+    // every compute unit gets one slice on top of its main tile (gemm_gu_fused_kernel)
+    const int ctiles = (N + 255) / 256, tiles = 2 * ctiles, rem = tiles % 256;
+    if (tiles > 256 && rem > 0 && rem <= 96) {
+      int best = 1;
+      for (int sp = 2; sp <= 16 && rem * sp <= 256; ++sp)
+        if (splits_valid(K, sp)) best = sp;
+      if (best > 1) {
+        ks.n_main = ((tiles - rem) / 2) * 256;
+        ks.rem_splits = best;
+      }
+    }
+  }
   return ks;
 }
 
@@ -397,6 +450,17 @@ int launch_gemm(const bf16_t *x, const bf16_t *w, void *y, float *ws, int M, int
     // columns go to a second launch of 64 x 128 tiles instead.
     const int ctiles = (N + 255) / 256, tiles = 2 * ctiles, rem = tiles % 256;
     if (tiles > 256 && rem > 0 && rem <= 64) n_main = ((tiles - rem) / 2) * 256;
+  }
+  if (mode == 1 && paired && n_main < N && ks.rem_splits > 1 && ks.splits == 1 && ws) {
+    // main tiles and K slices of the remainder in one launch, then the SwiGLU over the slices
+    if ((int64_t)N * K * 2 >= GEMM_MAX_OPERAND_BYTES || (int64_t)M * K * 2 >= GEMM_MAX_OPERAND_BYTES) return -1;
+    const int nrow = (M + 127) / 128, rem_ctiles = (N - n_main + 255) / 256;
+    const int wgs = std::max(((n_main / 256 + 7) / 8) * 8 * nrow, rem_ctiles * nrow * ks.rem_splits);
+    const int rem_ksteps = 4 * ((K / (4 * BK) + ks.rem_splits - 1) / ks.rem_splits);
+    hipLaunchKernelGGL((gemm_gu_fused_kernel<1, 4, 4, 2>), dim3(wgs), dim3(256), 0, s, x, w, (bf16_t *)y, ws, M, N, K, n_main,
+                       ks.rem_splits, rem_ksteps);
+    if (hipGetLastError() != hipSuccess) return -7;
+    return swiglu_reduce(ws, ks.rem_splits, M, N - n_main, n_main, (bf16_t *)y, N / 2, s);
   }
   int rc = launch_gemm_cfg(cfg, x, w, y, ws, M, N, K, mode, ks.splits, 0, n_main, paired, s);
   if (rc || n_main == N) return rc;

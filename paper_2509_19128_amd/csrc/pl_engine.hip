@@ -1438,6 +1438,30 @@ int pl_debug_gemm_cfg(int32_t cfg, const void *x, const void *w, void *y, void *
   return PL_OK;
 }
 
+int pl_debug_gemm_plan(int32_t M_max, int32_t N, int32_t K, int32_t mode, int32_t *splits, int32_t *n_main,
+                       int32_t *rem_splits, int64_t *ws_elems) {
+  if (M_max < 1 || M_max > 512 || N < 32 || K < 256 || (mode != 0 && mode != 1)) return fail(PL_E_INVAL, "unsupported GEMM shape");
+  const pl::GemmSplit ks = pl::gemm_pick_split(M_max, N, K, mode);
+  if (splits) *splits = ks.splits;
+  if (n_main) *n_main = ks.n_main;
+  if (rem_splits) *rem_splits = ks.rem_splits;
+  if (ws_elems) *ws_elems = pl::gemm_workspace_elems(M_max, N, ks);
+  return PL_OK;
+}
+
+int pl_debug_gemm_planned(const void *x, const void *w, void *y, void *ws, int32_t M_max, int32_t M, int32_t N, int32_t K,
+                          int32_t mode, void *stream) {
+  if (!x || !w || !y) return fail(PL_E_INVAL, "NULL argument");
+  if (M_max < 1 || M_max > 512 || M < 1 || M > M_max || N < 32 || K < 256 || (mode != 0 && mode != 1))
+    return fail(PL_E_INVAL, "unsupported GEMM shape");
+  const pl::GemmSplit ks = pl::gemm_pick_split(M_max, N, K, mode);
+  if (!ws && pl::gemm_workspace_elems(M_max, N, ks) > 0) return fail(PL_E_INVAL, "this plan needs a workspace");
+  int rc = pl::launch_gemm((const bf16_t *)x, (const bf16_t *)w, y, (float *)ws, M, N, K, mode, ks, (hipStream_t)stream);
+  if (rc == -1) return fail(PL_E_INVAL, "unsupported GEMM shape M=%d N=%d K=%d mode=%d", M, N, K, mode);
+  if (rc) return fail(PL_E_HIP, "GEMM launch failed");
+  return PL_OK;
+}
+
 int64_t pl_debug_stream_read(const void *device_ptr, int64_t nbytes, int32_t nontemporal, void *stream) {
   if (!device_ptr || nbytes < (int64_t)16 * 8192 * 2048) return fail(PL_E_INVAL, "need a device buffer of at least 256 MiB");
   int64_t r = pl::launch_stream_read(device_ptr, nbytes, nullptr, nontemporal != 0, (hipStream_t)stream);

@@ -247,6 +247,41 @@ def test_every_gemm_tile_configuration_against_fp64(cfg):
         assert ok, (splits, nb, ne, err)
 
 
+@pytest.mark.parametrize("F,K", [(18944, 3584), (18976, 768)])
+def test_swiglu_product_of_a_256_row_engine_is_the_same_for_every_row_count(F, K):
+    """An engine of 256 slots at a wide SwiGLU product: passes of 129..256 rows take the launch that gives every
+    compute unit a main tile and a K slice of the leftover columns, narrower passes separate launches with
+    the same slices.  Every row count against fp64, and the rows of a narrower pass bit-equal to the same
+    rows of the widest one.  The second shape ends in a ragged column tile."""
+    N, M_max = 2 * F, 256
+    splits, n_main, rem_splits, ws_elems = pl.pl_debug_gemm_plan(M_max, N, K, 1)
+    assert splits == 1 and 0 < n_main < N and rem_splits > 1 and ws_elems == rem_splits * M_max * (N - n_main)
+    rng = np.random.default_rng(F + K)
+    x = synth.bf16_round(rng.standard_normal((M_max, K), dtype=np.float32))
+    w = synth.bf16_round(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    xd, wd = dev_bf16(x), dev_bf16(pl.operand_order(w))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    gate = ref.reshape(M_max, N // 64, 2, 32)[:, :, 0].reshape(M_max, F)
+    up = ref.reshape(M_max, N // 64, 2, 32)[:, :, 1].reshape(M_max, F)
+    want = gate / (1.0 + np.exp(-gate)) * up
+    ws = torch.empty(ws_elems, device="cuda", dtype=torch.float32)
+    widest = None
+    for M in (256, 255, 200, 129, 128, 65, 64, 20, 1):
+        mid = torch.full((M, F), float("nan"), device="cuda", dtype=torch.bfloat16)
+        ws.fill_(float("nan"))
+        pl.pl_debug_gemm_planned(xd.data_ptr(), wd.data_ptr(), mid.data_ptr(), ws.data_ptr(), M_max, M, N, K, 1, 0)
+        torch.cuda.synchronize()
+        got = to_np(mid)
+        ok, err = close(got, want[:M], 2e-3, RTOL)
+        assert ok, (M, err)
+        if widest is None:
+            widest = got
+        else:
+            assert np.array_equal(got, widest[:M]), M
+    with pytest.raises(pl.PlError):
+        pl.pl_debug_gemm_planned(xd.data_ptr(), wd.data_ptr(), mid.data_ptr(), 0, M_max, 200, N, K, 1, 0)
+
+
 def test_gemm_rejects_bad_shapes():
     t = torch.zeros(600 * 512, device="cuda", dtype=torch.bfloat16)
     for args in [(4, 64, 192, 0, 1), (0, 64, 256, 0, 1), (4, 64, 512, 0, 3), (4, 96, 256, 1, 1), (4, 64, 512, 1, 2),
