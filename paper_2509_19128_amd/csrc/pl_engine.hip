@@ -1445,7 +1445,7 @@ int pl_debug_gemm_plan(int32_t M_max, int32_t N, int32_t K, int32_t mode, int32_
   if (splits) *splits = ks.splits;
   if (n_main) *n_main = ks.n_main;
   if (rem_splits) *rem_splits = ks.rem_splits;
-  if (ws_elems) *ws_elems = pl::gemm_workspace_elems(M_max, N, ks);
+  if (ws_elems) *ws_elems = mode == 1 ? pl::gemm_workspace_elems(M_max, N, ks) : 0;   // mode 0 keeps its slices in y
   return PL_OK;
 }
 
@@ -1455,7 +1455,7 @@ int pl_debug_gemm_planned(const void *x, const void *w, void *y, void *ws, int32
   if (M_max < 1 || M_max > 512 || M < 1 || M > M_max || N < 32 || K < 256 || (mode != 0 && mode != 1))
     return fail(PL_E_INVAL, "unsupported GEMM shape");
   const pl::GemmSplit ks = pl::gemm_pick_split(M_max, N, K, mode);
-  if (!ws && pl::gemm_workspace_elems(M_max, N, ks) > 0) return fail(PL_E_INVAL, "this plan needs a workspace");
+  if (!ws && mode == 1 && pl::gemm_workspace_elems(M_max, N, ks) > 0) return fail(PL_E_INVAL, "this plan needs a workspace");
   int rc = pl::launch_gemm((const bf16_t *)x, (const bf16_t *)w, y, (float *)ws, M, N, K, mode, ks, (hipStream_t)stream);
   if (rc == -1) return fail(PL_E_INVAL, "unsupported GEMM shape M=%d N=%d K=%d mode=%d", M, N, K, mode);
   if (rc) return fail(PL_E_HIP, "GEMM launch failed");

@@ -373,3 +373,28 @@ def test_tied_embeddings_blob_has_no_lm_head():
     e.load_weights(blob)
     e.add_sequence(1, [1, 2], 2)
     assert e.decode_step()["n"] == 1
+
+
+def test_gemm_plan_is_a_function_of_the_largest_row_count_only():
+    """The K split an engine fixes for its products (host logic only).  Every slice must be non-empty in units
+    of 4 k-steps of 64; the SwiGLU product is split only where the 7B shape leaves 40 of 296 tiles over, and
+    then into as many slices as give each of the 256 compute units one."""
+    def slices_ok(K, s):
+        units = K // 256
+        return 1 <= s <= units and (s - 1) * -(-units // s) < units
+    # SwiGLU products: 7B at 256 slots, the same at 128 slots, 1.5B, 32B
+    assert pl.pl_debug_gemm_plan(256, 2 * 18944, 3584, 1) == (1, 32768, 5, 5 * 256 * (2 * 18944 - 32768))
+    assert pl.pl_debug_gemm_plan(200, 2 * 18944, 3584, 1)[:3] == (1, 32768, 5)
+    assert pl.pl_debug_gemm_plan(128, 2 * 18944, 3584, 1) == (1, 2 * 18944, 1, 0)
+    assert pl.pl_debug_gemm_plan(64, 2 * 8960, 1536, 1) == (1, 2 * 8960, 1, 0)
+    assert pl.pl_debug_gemm_plan(256, 2 * 8960, 1536, 1) == (1, 2 * 8960, 1, 0)       # narrower than 128 x 256 tiles
+    assert pl.pl_debug_gemm_plan(256, 2 * 16384, 3584, 1) == (1, 2 * 16384, 1, 0)      # exactly one round of tiles
+    # plain products: one split count for all columns, never an empty slice
+    for M_max in (1, 32, 64, 128, 256, 512):
+        for N, K in [(4608, 3584), (3584, 3584), (3584, 18944), (2048, 1536), (1536, 8960), (7168, 5120), (5120, 27648),
+                     (152064, 3584)]:
+            s, n_main, rs, ws = pl.pl_debug_gemm_plan(M_max, N, K, 0)
+            assert n_main == N and rs == 1 and ws == 0 and slices_ok(K, s), (M_max, N, K, s)
+    for bad in [(0, 4608, 3584, 0), (513, 4608, 3584, 0), (256, 4608, 3584, 2), (256, 16, 3584, 0)]:
+        with pytest.raises(pl.PlError):
+            pl.pl_debug_gemm_plan(*bad)
