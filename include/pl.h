@@ -108,7 +108,8 @@ typedef struct {
   /* filled while profiling is on (pl_debug_set_profile): GPU time between HIP events recorded on the
    * decode stream around each kernel group, summed over steps */
   double attn_ms, gemm_ms, sample_ms, other_ms;
-  uint64_t attn_launches, gemm_launches; /* attention launches (one per layer per step), GEMM launches */
+  uint64_t attn_launches, gemm_launches; /* launches of the decode-attention kernel (one per layer per step; the kernel
+                                          * that merges the chunks of long rows is timed under other_ms), GEMM launches */
   double attn_kv_bytes;                  /* K/V bytes those attention launches had to read */
   /* the part of the three attention figures above that was measured in steps during which a background
    * cache-only pass (pl_prefill_async) was in flight, i.e. while the kernel shared the GPU */

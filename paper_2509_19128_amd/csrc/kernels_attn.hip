@@ -343,23 +343,25 @@ int launch_attention_worklist(const int32_t *ctx_len, const int32_t *row_slot, c
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }
 
-int launch_attention(const AttnParams &p, hipStream_t s) {
+// part: 0 = the decode kernel and, where a row spans several chunks, the merge kernel; 1 = the decode
+// kernel alone; 2 = the merge kernel alone (so that a caller can time the two separately)
+int launch_attention(const AttnParams &p, hipStream_t s, int part) {
   if (p.n_seq <= 0) return 0;
   // max_items and max_multi bound the two lists (a host that knows the step's contexts passes the
   // exact lengths; otherwise n_seq * max_chunks and n_seq)
   dim3 grid(p.max_items * p.Hkv), cgrid(p.Hq, p.max_multi > 0 ? p.max_multi : 1);
-  const bool merge = p.max_multi > 0;
+  const bool decode = part != 2, merge = p.max_multi > 0 && part != 1;
   switch (p.hd) {
     case 128:
-      hipLaunchKernelGGL((attn_decode_kernel<128, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
+      if (decode) hipLaunchKernelGGL((attn_decode_kernel<128, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
       if (merge) hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(128), 0, s, p);
       break;
     case 64:
-      hipLaunchKernelGGL((attn_decode_kernel<64, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
+      if (decode) hipLaunchKernelGGL((attn_decode_kernel<64, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
       if (merge) hipLaunchKernelGGL(attn_combine_kernel<64>, cgrid, dim3(64), 0, s, p);
       break;
     case 32:
-      hipLaunchKernelGGL((attn_decode_kernel<32, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
+      if (decode) hipLaunchKernelGGL((attn_decode_kernel<32, PL_ATTN_NS>), grid, dim3(256), 0, s, p);
       if (merge) hipLaunchKernelGGL(attn_combine_kernel<32>, cgrid, dim3(64), 0, s, p);
       break;
     default:

@@ -255,19 +255,21 @@ __global__ __launch_bounds__(256) void gemm_gu_fused_kernel(const bf16_t *__rest
 // mid[m][(col0 + c) / 2 ...] = silu(sum_s gate) * (sum_s up), slices added in order.
 __global__ __launch_bounds__(256) void swiglu_reduce_kernel(const float *__restrict__ parts, int splits, int M, int ld,
                                                             int col0, bf16_t *__restrict__ mid, int F) {
-  const int half_ld = ld >> 1;
+  const int quads = ld >> 3;   // four outputs per thread (ld is a multiple of 64)
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (int64_t)M * half_ld) return;
-  const int m = (int)(idx / half_ld), j = (int)(idx % half_ld);
+  if (idx >= (int64_t)M * quads) return;
+  const int m = (int)(idx / quads), j = (int)(idx % quads) * 4;
   const int c = (j >> 5) * 64 + (j & 31);
-  float g = 0.f, u = 0.f;
+  f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
   for (int sl = 0; sl < splits; ++sl) {
     const float *row = parts + ((int64_t)sl * M + m) * ld;
-    g += row[c];
-    u += row[c + 32];
+    g += *(const f32x4 *)(row + c);
+    u += *(const f32x4 *)(row + c + 32);
   }
-  const float sv = g / (1.f + __expf(-g));
-  mid[(int64_t)m * F + (col0 >> 1) + j] = (__bf16)(sv * u);
+  bf16x4 o;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = (__bf16)(g[i] / (1.f + __expf(-g[i])) * u[i]);
+  *(bf16x4 *)(mid + (int64_t)m * F + (col0 >> 1) + j) = o;
 }
 
 struct Launch {
@@ -324,7 +326,7 @@ bool splits_valid(int K, int splits) {
 }
 
 int swiglu_reduce(const float *parts, int splits, int M, int ld, int col0, bf16_t *mid, int F, hipStream_t s) {
-  const int64_t total = (int64_t)M * (ld / 2);
+  const int64_t total = (int64_t)M * (ld / 8);
   hipLaunchKernelGGL(swiglu_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, parts, splits, M, ld, col0, mid, F);
   return hipGetLastError() == hipSuccess ? 0 : -7;
 }

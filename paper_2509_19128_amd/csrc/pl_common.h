@@ -39,7 +39,7 @@ struct AttnParams {
   float *part_ml;           // [n_seq, Hkv, max_chunks, G, 2]
   int32_t n_seq, Hq, Hkv, hd, page_tokens, pages_per_seq, chunk, max_chunks;
 };
-int launch_attention(const AttnParams &p, hipStream_t s);
+int launch_attention(const AttnParams &p, hipStream_t s, int part = 0);
 int64_t attention_worklist_ints(int n_seq, int max_chunks);
 const int32_t *attention_multi_list(const int32_t *work, int n_seq, int max_chunks);
 int launch_attention_worklist(const int32_t *ctx_len, const int32_t *row_slot, const int32_t *page_table, int32_t *work,

@@ -451,9 +451,15 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
     ap.work = w.attn_work; ap.max_items = w.attn_items;
     ap.multi = pl::attention_multi_list(w.attn_work, n, e->attn_max_chunks); ap.max_multi = w.attn_multi;
     if (prefill && l + 1 == c.n_layers) break;
-    if (timed) mark(e, CAT_OTHER, true);
-    rc |= pl::launch_attention(ap, s);
-    if (timed) mark(e, CAT_ATTN, true);
+    if (timed && e->profile) {   // the timers bracket the decode kernel alone; the merge kernel counts as "other"
+      mark(e, CAT_OTHER, true);
+      rc |= pl::launch_attention(ap, s, 1);
+      mark(e, CAT_ATTN, true);
+      rc |= pl::launch_attention(ap, s, 2);
+      mark(e, CAT_OTHER);
+    } else {
+      rc |= pl::launch_attention(ap, s);
+    }
     rc |= pl::launch_gemm(w.attn_out, lw.w_o, w.parts, nullptr, n, d, qd, 0, e->ks_o, s);
     if (timed) mark(e, CAT_GEMM);
     rc |= pl::launch_resid_rmsnorm(w.h, w.parts, e->ks_o.splits, lw.g2, w.a, n, d, c.rms_eps, s);
@@ -1129,6 +1135,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     }
     HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
     HIP_TRY(hipEventRecord(e->ev_a, s));
+    e->prof_n = 0;   // a replayed graph records no per-kernel events: nothing of an earlier step may be counted again
     int rc = run_step(e, w, n);
     if (rc) return rc;
     HIP_TRY(hipEventRecord(e->ev_b, s));
