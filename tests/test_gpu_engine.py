@@ -698,6 +698,32 @@ def test_steps_replayed_from_a_graph_equal_steps_launched_kernel_by_kernel(weigh
     assert len(shapes) >= 3       # the run did go through several launch shapes
 
 
+def test_per_kernel_timers_count_only_the_steps_they_were_on_for(weights):
+    """The benchmark switches the timers on for some steps of its window only: a step with timers launches
+    its kernels one by one and counts one attention launch per layer; a replayed step records no events and
+    must leave the counters alone; the tokens are the same either way."""
+    master, _ = weights
+    rng_p = np.random.default_rng(71)
+    eng = _engine(max_batch=4)
+    eng.load_weights(eng.pack_weights(master, synth.f32_to_bf16_bits))
+    for i in range(4):
+        eng.add_sequence(i, rng_p.integers(0, M.vocab, 6).astype(np.int32), 40)
+    seen = []
+    for step in range(12):
+        on = step % 4 == 0
+        eng.debug_set_profile(1 if on else 0)
+        before = eng.stats()
+        eng.decode_step()
+        after = eng.stats()
+        seen.append(after["attn_launches"] - before["attn_launches"])
+        if on:
+            assert after["attn_ms"] > before["attn_ms"] and after["attn_kv_bytes"] > before["attn_kv_bytes"]
+        else:
+            assert after["attn_ms"] == before["attn_ms"] and after["attn_kv_bytes"] == before["attn_kv_bytes"]
+    assert seen == [M.n_layers if s % 4 == 0 else 0 for s in range(12)]
+    eng.close()
+
+
 def test_more_launch_shapes_than_the_graph_cache_holds(weights):
     """Row counts 1..40 in turn (more shapes than cached graphs, so the least recently used ones are dropped
     and captured again later): every step equals the eager engine's, bit for bit."""
