@@ -114,37 +114,48 @@ __global__ void rope_tables_kernel(const int32_t *pos, float *cs, int32_t *ctx_l
 }
 
 // qkv (fp32, split-K partials) -> rotated q (bf16), rotated k and v into the row's cache page.
-// One thread per rotated pair (or pair of value elements); a workgroup of 256 threads covers 256
-// consecutive pairs of one row, i.e. several heads of q|k|v.
+// One thread per four consecutive rotated pairs (i .. i + 3 with their partners half + i ..), 16-byte
+// loads; a workgroup of 256 threads covers 1024 consecutive pairs of one row, i.e. several heads of q|k|v.
 __global__ __launch_bounds__(256) void rope_append_kernel(const float *qkv, int splits, const float *cs, const int32_t *pos,
                                                           const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out,
                                                           bf16_t *kv_layer, int n, int Hq, int Hkv, int hd, int page_tokens,
                                                           int pages_per_seq) {
-  const int half = hd / 2;
-  const int pair = blockIdx.x * 256 + threadIdx.x;
-  if (pair >= (Hq + 2 * Hkv) * half) return;
-  const int row = blockIdx.y, hh = pair / half, i = pair % half;
+  const int half = hd / 2, quads = half / 4;
+  const int quad = blockIdx.x * 256 + threadIdx.x;
+  if (quad >= (Hq + 2 * Hkv) * quads) return;
+  const int row = blockIdx.y, hh = quad / quads, i = (quad % quads) * 4;
   const int width = (Hq + 2 * Hkv) * hd;
-  float x1 = 0.f, x2 = 0.f;
+  f32x4 x1 = {0.f, 0.f, 0.f, 0.f}, x2 = {0.f, 0.f, 0.f, 0.f};
   // loads of up to 8 slices are issued together, the adds stay in slice order
   for (int s0 = 0; s0 < splits; s0 += 8) {
-    float p1[8], p2[8];
+    f32x4 p1[8], p2[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
       if (s0 + u < splits) {
         const float *src = qkv + ((int64_t)(s0 + u) * n + row) * width + hh * hd;
-        p1[u] = src[i];
-        p2[u] = src[half + i];
+        p1[u] = *(const f32x4 *)(src + i);
+        p2[u] = *(const f32x4 *)(src + half + i);
       }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
       if (s0 + u < splits) { x1 += p1[u]; x2 += p2[u]; }
   }
+  bf16x4 lo, hi;   // elements i .. i + 3 and half + i .. half + i + 3 of the head
+  if (hh < Hq + Hkv) {
+    const f32x4 c = *(const f32x4 *)(cs + (int64_t)row * hd + i), sn = *(const f32x4 *)(cs + (int64_t)row * hd + half + i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      lo[e] = (__bf16)(x1[e] * c[e] - x2[e] * sn[e]);
+      hi[e] = (__bf16)(x2[e] * c[e] + x1[e] * sn[e]);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { lo[e] = (__bf16)x1[e]; hi[e] = (__bf16)x2[e]; }
+  }
   if (hh < Hq) {
-    const float c = cs[(int64_t)row * hd + i], sn = cs[(int64_t)row * hd + half + i];
     bf16_t *q = q_out + ((int64_t)row * Hq + hh) * hd;
-    q[i] = (__bf16)(x1 * c - x2 * sn);
-    q[half + i] = (__bf16)(x2 * c + x1 * sn);
+    *(bf16x4 *)(q + i) = lo;
+    *(bf16x4 *)(q + half + i) = hi;
     return;
   }
   const int p = pos[row];
@@ -152,14 +163,17 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *qkv, int 
   const int t = p % page_tokens;
   const int64_t page_elems = (int64_t)2 * page_tokens * hd;
   if (hh < Hq + Hkv) {
-    const float c = cs[(int64_t)row * hd + i], sn = cs[(int64_t)row * hd + half + i];
+    // four consecutive dims of a token (i is a multiple of 4) are contiguous in the K block
     bf16_t *kb = kv_layer + ((int64_t)page * Hkv + (hh - Hq)) * page_elems;
-    kb[k_elem_offset(t, i, hd)] = (__bf16)(x1 * c - x2 * sn);
-    kb[k_elem_offset(t, half + i, hd)] = (__bf16)(x2 * c + x1 * sn);
+    *(bf16x4 *)(kb + k_elem_offset(t, i, hd)) = lo;
+    *(bf16x4 *)(kb + k_elem_offset(t, half + i, hd)) = hi;
   } else {
     bf16_t *vb = kv_layer + ((int64_t)page * Hkv + (hh - Hq - Hkv)) * page_elems + (int64_t)page_tokens * hd;
-    vb[v_elem_offset(t, i, hd)] = (__bf16)x1;
-    vb[v_elem_offset(t, half + i, hd)] = (__bf16)x2;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vb[v_elem_offset(t, i + e, hd)] = lo[e];
+      vb[v_elem_offset(t, half + i + e, hd)] = hi[e];
+    }
   }
 }
 
@@ -235,7 +249,7 @@ int launch_rope_append(const float *qkv, int splits, const float *cs, const int3
                        const int32_t *row_slot, const int32_t *page_table, bf16_t *q_out, bf16_t *kv_layer,
                        int n, int Hq, int Hkv, int hd, int page_tokens, int pages_per_seq, hipStream_t s) {
   if (n <= 0) return 0;
-  hipLaunchKernelGGL(rope_append_kernel, dim3(((Hq + 2 * Hkv) * (hd / 2) + 255) / 256, n), dim3(256), 0, s, qkv, splits, cs, pos, row_slot,
+  hipLaunchKernelGGL(rope_append_kernel, dim3(((Hq + 2 * Hkv) * (hd / 8) + 255) / 256, n), dim3(256), 0, s, qkv, splits, cs, pos, row_slot,
                      page_table, q_out, kv_layer, n, Hq, Hkv, hd, page_tokens, pages_per_seq);
   return ok();
 }
