@@ -282,6 +282,34 @@ def test_swiglu_product_of_a_256_row_engine_is_the_same_for_every_row_count(F, K
         pl.pl_debug_gemm_planned(xd.data_ptr(), wd.data_ptr(), mid.data_ptr(), 0, M_max, 200, N, K, 1, 0)
 
 
+@pytest.mark.parametrize("M_max,N,K", [(256, 4608, 3584), (256, 3584, 18944), (64, 2048, 1536), (128, 7168, 5120)])
+def test_plain_products_of_an_engine_are_the_same_for_every_row_count(M_max, N, K):
+    """QKV- and down-shaped products as an engine of M_max slots launches them: the tile shape follows the rows
+    of the call, the K split is fixed, so every slice of the partial sums of a narrow pass is bit-equal to the
+    same rows of the widest pass; their sum is the product."""
+    splits, n_main, rem_splits, ws_elems = pl.pl_debug_gemm_plan(M_max, N, K, 0)
+    assert n_main == N and ws_elems == 0
+    rng = np.random.default_rng(N + K)
+    x = synth.bf16_round(rng.standard_normal((M_max, K), dtype=np.float32))
+    w = synth.bf16_round(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    xd, wd = dev_bf16(x), dev_bf16(pl.operand_order(w))
+    ref = x.astype(np.float64) @ w.astype(np.float64).T
+    widest = None
+    for M in sorted({M_max, M_max - 1, 200, 129, 128, 65, 64, 33, 32, 5, 1}, reverse=True):
+        if M > M_max:
+            continue
+        y = torch.full((splits, M, N), float("nan"), device="cuda", dtype=torch.float32)
+        pl.pl_debug_gemm_planned(xd.data_ptr(), wd.data_ptr(), y.data_ptr(), 0, M_max, M, N, K, 0, 0)
+        torch.cuda.synchronize()
+        got = to_np(y)
+        if widest is None:
+            widest = got
+            ok, err = close(got.astype(np.float64).sum(0), ref, 1e-4 * np.sqrt(K) * 0.05, 1e-4)
+            assert ok, err
+        else:
+            assert np.array_equal(got, widest[:, :M]), M
+
+
 def test_gemm_rejects_bad_shapes():
     t = torch.zeros(600 * 512, device="cuda", dtype=torch.bfloat16)
     for args in [(4, 64, 192, 0, 1), (0, 64, 256, 0, 1), (4, 64, 512, 0, 3), (4, 96, 256, 1, 1), (4, 64, 512, 1, 2),
