@@ -811,7 +811,7 @@ def main():
         res["roofline"] = {"bound": "hbm", "kernel": "attn_decode_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                            "launches": int(alone or d["attn_launches"]),
-                           "timed_on": f"every {prof_every}. step of the timed window" if prof_every > 1 else "every timed step",
+                           "timed_on": f"one timed step in {prof_every}" if prof_every > 1 else "every timed step",
                            "launches_beside_a_background_pass": int(d["attn_shared_launches"]),
                            "achieved_beside_a_background_pass": (d["attn_shared_kv_bytes"] / d["attn_shared_ms"] / 1e6
                                                                  if d["attn_shared_launches"] else None),
