@@ -94,7 +94,7 @@ struct pl_engine {
   // kv
   char *kv_pool = nullptr;   // bf16 pages in operand order, or fp32 pages of the test build
   std::vector<int32_t> free_pages;
-  int32_t *pt_h = nullptr, *pt_d = nullptr;
+  int32_t *pt_h = nullptr;   // host page table (pinned): the truth; each work set keeps a device copy of its own
   bool pt_dirty = false;
   std::vector<Seq> seqs;
   // Activation buffers and per-pass metadata come in two sets, each with its own stream: set 0 is the
@@ -107,6 +107,7 @@ struct pl_engine {
     float *h = nullptr, *parts = nullptr, *cs = nullptr, *attn_po = nullptr, *attn_pml = nullptr;
     bf16_t *a = nullptr, *q_rot = nullptr, *attn_out = nullptr, *mid = nullptr;
     int32_t *ctx_len = nullptr, *attn_work = nullptr;
+    int32_t *pt = nullptr;   // device copy of the page table, written on this set's stream only
     int attn_items = 0;   // bound on this pass's attention work items
     int attn_multi = 0;   // rows of this pass that span more than one attention chunk
     // the 8-byte ids come first, so every array is aligned for its type whatever rows_cap is
@@ -256,6 +257,7 @@ int alloc_work(pl_engine *e, pl_engine::Work &w, int64_t R, int64_t parts_elems,
   if ((rc = dev_alloc(&w.mid, R * c.d_ffn * wide))) return rc;
   if ((rc = dev_alloc(&w.cs, R * c.head_dim))) return rc;
   if ((rc = dev_alloc(&w.ctx_len, R))) return rc;
+  if ((rc = dev_alloc(&w.pt, (int64_t)c.max_batch * e->pages_per_seq))) return rc;
   const int64_t np = R * c.n_kv_heads * e->attn_max_chunks * e->G;
   if ((rc = dev_alloc(&w.attn_po, np * c.head_dim))) return rc;
   if ((rc = dev_alloc(&w.attn_pml, np * 2))) return rc;
@@ -265,7 +267,7 @@ int alloc_work(pl_engine *e, pl_engine::Work &w, int64_t R, int64_t parts_elems,
 }
 
 void free_work(pl_engine::Work &w) {
-  void *dev[] = {w.meta_d, w.h, w.a, w.parts, w.q_rot, w.attn_out, w.mid, w.cs, w.ctx_len, w.attn_po, w.attn_pml, w.attn_work};
+  void *dev[] = {w.meta_d, w.h, w.a, w.parts, w.q_rot, w.attn_out, w.mid, w.cs, w.ctx_len, w.pt, w.attn_po, w.attn_pml, w.attn_work};
   for (void *p : dev)
     if (p) (void)hipFree(p);
   w = pl_engine::Work{};
@@ -306,7 +308,6 @@ int alloc_device(pl_engine *e) {
   // how many rows a pass holds
   e->attn_chunk = pl::attention_chunk_tokens(B, c.n_kv_heads, c.max_context);
   e->attn_max_chunks = (c.max_context + e->attn_chunk - 1) / e->attn_chunk;
-  if ((rc = dev_alloc(&e->pt_d, (int64_t)B * e->pages_per_seq))) return rc;
   if ((rc = alloc_work(e, e->wk[0], R, parts, true))) return rc;
   if ((rc = alloc_work(e, e->wk[1], R, parts, false))) return rc;
   e->ring.resize(PASS_RING);
@@ -390,10 +391,10 @@ int enqueue_step_f32(pl_engine *e, pl_engine::Work &w, int n, bool prefill) {
     const size_t t0 = 1 + (size_t)l * 6;   // g1, w_qkv, w_o, g2, w_gu, w_d
     float *kv_layer = (float *)e->kv_pool + (int64_t)l * e->layer_stride;
     rc |= pl::f32_launch_gemm(a, T(t0 + 1), w.parts, n, wq, d, s);
-    rc |= pl::f32_launch_rope_append(w.parts, w.cs, w.m_pos(true), w.m_row_slot(true), e->pt_d, q_rot, kv_layer, n,
+    rc |= pl::f32_launch_rope_append(w.parts, w.cs, w.m_pos(true), w.m_row_slot(true), w.pt, q_rot, kv_layer, n,
                                      c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens, e->pages_per_seq, s);
     if (prefill && l + 1 == c.n_layers) break;
-    rc |= pl::f32_launch_attention(q_rot, kv_layer, e->pt_d, w.m_pos(true), w.m_row_slot(true), attn_out, n, c.n_q_heads,
+    rc |= pl::f32_launch_attention(q_rot, kv_layer, w.pt, w.m_pos(true), w.m_row_slot(true), attn_out, n, c.n_q_heads,
                                    c.n_kv_heads, c.head_dim, e->page_tokens, e->pages_per_seq, s);
     rc |= pl::f32_launch_gemm(attn_out, T(t0 + 2), w.parts, n, d, qd, s);
     rc |= pl::f32_launch_norm(nullptr, nullptr, 0, w.parts, T(t0 + 3), w.h, a, n, d, c.rms_eps, s);
@@ -428,7 +429,7 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
   const bf16_t *lm = base + e->layout.back().offset;
   int rc = 0;
   rc |= pl::launch_rope_tables(w.m_pos(true), w.cs, w.ctx_len, n, c.head_dim, c.rope_theta, s);
-  rc |= pl::launch_attention_worklist(w.ctx_len, w.m_row_slot(true), e->pt_d, w.attn_work, n, e->attn_max_chunks,
+  rc |= pl::launch_attention_worklist(w.ctx_len, w.m_row_slot(true), w.pt, w.attn_work, n, e->attn_max_chunks,
                                       e->attn_chunk, e->page_tokens, e->pages_per_seq, s);
   const bf16_t *g_first = c.n_layers ? layer_weights(e, 0).g1 : gf;
   rc |= pl::launch_embed_rmsnorm(embed, g_first, w.m_input(true), nullptr, w.m_row_slot(true), w.h, w.a, n,
@@ -439,11 +440,11 @@ int enqueue_step(pl_engine *e, pl_engine::Work &w, int n, bool prefill = false) 
     if (timed) mark(e, CAT_OTHER);
     rc |= pl::launch_gemm(w.a, lw.w_qkv, w.parts, nullptr, n, wq, d, 0, e->ks_qkv, s);
     if (timed) mark(e, CAT_GEMM);
-    rc |= pl::launch_rope_append(w.parts, e->ks_qkv.splits, w.cs, w.m_pos(true), w.m_row_slot(true), e->pt_d,
+    rc |= pl::launch_rope_append(w.parts, e->ks_qkv.splits, w.cs, w.m_pos(true), w.m_row_slot(true), w.pt,
                                  w.q_rot, kv_layer, n, c.n_q_heads, c.n_kv_heads, c.head_dim, e->page_tokens,
                                  e->pages_per_seq, s);
     pl::AttnParams ap{};
-    ap.q = w.q_rot; ap.kv = kv_layer; ap.page_table = e->pt_d; ap.ctx_len = w.ctx_len;
+    ap.q = w.q_rot; ap.kv = kv_layer; ap.page_table = w.pt; ap.ctx_len = w.ctx_len;
     ap.row_slot = w.m_row_slot(true); ap.out = w.attn_out; ap.part_o = w.attn_po; ap.part_ml = w.attn_pml;
     ap.n_seq = n; ap.Hq = c.n_q_heads; ap.Hkv = c.n_kv_heads; ap.hd = c.head_dim;
     ap.page_tokens = e->page_tokens; ap.pages_per_seq = e->pages_per_seq; ap.chunk = e->attn_chunk;
@@ -667,10 +668,11 @@ int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::ve
       w.attn_items = items;
       w.attn_multi = multi;
       hipStream_t s = w.stream;
-      // The page table goes up on this stream too (the same bytes a decode step would send: the host
-      // table is the truth); the dirty flag stays, the decode stream sends its own copy.
+      // The page table goes up on this stream into this set's own device copy (no device buffer is ever
+      // written from two streams); the rows of the slots being read do not change while they are read.
+      // The dirty flag stays: the decode stream sends the table to its own copy.
       if (r0 == 0)
-        HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
+        HIP_TRY(hipMemcpyAsync(w.pt, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
       HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
       HIP_TRY(hipEventRecord(im.ev_begin, s));
       int rc = run_step(e, w, n, true);
@@ -769,7 +771,7 @@ void pl_destroy(pl_engine *e) {
     if (e->s_dec) (void)hipStreamSynchronize(e->s_dec);
     if (e->s_copy) (void)hipStreamSynchronize(e->s_copy);
     if (e->wk[1].stream) (void)hipStreamSynchronize(e->wk[1].stream);
-    void *dev[] = {e->wbuf[0], e->wbuf[1], e->kv_pool, e->pt_d, e->logits, e->tok_d, e->lp_d, e->samp_ws};
+    void *dev[] = {e->wbuf[0], e->wbuf[1], e->kv_pool, e->logits, e->tok_d, e->lp_d, e->samp_ws};
     for (void *p : dev)
       if (p) (void)hipFree(p);
     void *hst[] = {e->pt_h, e->wk[0].meta_h, e->tok_h, e->lp_h};
@@ -1130,7 +1132,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     HIP_TRY(hipSetDevice(c.device));
     hipStream_t s = e->s_dec;
     if (e->pt_dirty) {
-      HIP_TRY(hipMemcpyAsync(e->pt_d, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(hipMemcpyAsync(w.pt, e->pt_h, (size_t)c.max_batch * e->pages_per_seq * 4, hipMemcpyHostToDevice, s));
       e->pt_dirty = false;
     }
     HIP_TRY(hipMemcpyAsync(w.meta_d, w.meta_h, (size_t)e->meta_bytes, hipMemcpyHostToDevice, s));
