@@ -1070,7 +1070,9 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     if (!e->staged && !e->dry && e->poison_inactive && c.n_weight_buffers == 2) {
       // Nothing may read the old weights after the flip: with every element a bf16 NaN, a kernel that
       // still does shows up in the logits.  The next staging copy overwrites the buffer; it cannot start
-      // before this step has ended (steps are synchronous), so the fill needs no further ordering.
+      // before this step has ended (steps are synchronous).  A prompt being read in the background was
+      // enqueued under the old weights and is entitled to them: the fill waits for the last such pass.
+      if (e->pre_pending) HIP_TRY(hipStreamWaitEvent(e->s_dec, e->ev_pre_last, 0));
       if (pl::launch_fill_u32((uint32_t *)e->wbuf[e->active_buf ^ 1], e->f32 ? 0x7FC00000u : 0x7FC07FC0u,
                               e->blob_elems * e->esz / 4, e->s_dec))
         return fail(PL_E_HIP, "fill launch failed");

@@ -615,12 +615,14 @@ def test_background_prompt_reading_equals_the_blocking_one_and_the_oracle(weight
 
 def test_background_prompt_reading_across_an_update_and_a_retire(weights):
     """The prompt is read under the weights active when the reading was requested, even if an update
-    becomes active before it ends; retiring a slot that is still reading waits for its passes."""
+    becomes active before it ends; retiring a slot that is still reading waits for its passes.  The buffer
+    that goes inactive at the flip is poisoned here: the fill must wait for the passes that still read it."""
     master, pert = weights
     prompts = synth.random_prompts(np.random.default_rng(33), 2, 70, M.vocab)
     eng = _engine(max_batch=4, max_context=256, kv_pool_tokens=4 * 256)
     blobs = [eng.pack_weights(w, synth.f32_to_bf16_bits) for w in (master, pert)]
     eng.load_weights(blobs[0])
+    eng.debug_set_poison(True)
     ref = _engine(max_batch=4, max_context=256, kv_pool_tokens=4 * 256)
     ref.load_weights(blobs[0])
     for e in (eng, ref):
