@@ -204,6 +204,204 @@ __device__ __forceinline__ void gemm_tile(bf16_t (*xs)[WM * AT * 32 * LDS_ROW], 
   }
 }
 
+// Two tiles back to back in one workgroup without draining the pipeline between them: tile A (all of
+// K, SwiGLU epilogue into mid, columns below n_main) and then K slice `split` of tile B (fp32 partial
+// sums into ws, as gemm_tile<MODE 0> writes them).  The last k-steps of A, which have nothing of their
+// own left to load, issue the first loads of B into the ring slots they free, so B starts with its
+// operands already on the way while A's epilogue runs.  Same k order per output element as gemm_tile.
+// K / BK and B's k-step count are multiples of 4 and at least 4.
+template <int WM, int WN, int AT, int BT>
+__device__ __forceinline__ void gemm_tile2(bf16_t (*xs)[WM * AT * 32 * LDS_ROW], const bf16_t *__restrict__ X,
+                                           const bf16_t *__restrict__ W, bf16_t *__restrict__ mid, float *__restrict__ ws,
+                                           int M, int N, int K, int n_tileA, int m0A, int n_main, int n_tileB, int m0B,
+                                           int split, int kstepsB) {
+  constexpr int BM = WM * AT * 32;
+  constexpr int XCH = BM * (BK / 8) / 256;
+  static_assert(WM * WN == 4 && XCH >= 1 && BT == 2, "tile");
+  const int tid = threadIdx.x, l = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int n0A = n_tileA + wn * BT * 32, n0B = n_tileB + wn * BT * 32;
+  const int nksA = K / BK;
+  const int nksB = min(kstepsB, K / BK - split * kstepsB);
+  const int lrow = l & 31, half = l >> 5;
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)W, 0, (int)((int64_t)N * K * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)X, 0, (int)((int64_t)M * K * 2), 0x00020000);
+  const int w_lane = l * 16;
+  const uint32_t w_plane = (uint32_t)(N >> 5) * 4096u;
+  uint32_t w_blkA[BT], w_blkB[BT];
+#pragma unroll
+  for (int bt = 0; bt < BT; ++bt) {
+    w_blkA[bt] = (uint32_t)min((n0A >> 5) + bt, (N >> 5) - 1) * 4096u;
+    w_blkB[bt] = (uint32_t)(split * kstepsB) * w_plane + (uint32_t)min((n0B >> 5) + bt, (N >> 5) - 1) * 4096u;
+  }
+  const int x_laneA = ((m0A + (tid >> 3)) * K + (tid & 7) * 8) * 2;
+  const int x_laneB = ((m0B + (tid >> 3)) * K + split * kstepsB * BK + (tid & 7) * 8) * 2;
+  const int x_lds = (tid >> 3) * LDS_ROW + (tid & 7) * 8;
+
+  f32x16 acc[AT][BT];
+  auto zero_acc = [&]() {
+#pragma unroll
+    for (int a = 0; a < AT; ++a)
+#pragma unroll
+      for (int b = 0; b < BT; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  };
+  zero_acc();
+
+  bf16x8 wf[4][BT][4], xr[2][XCH];
+  // SEG: 1 = tile A, 2 = tile B
+  auto load_w = [&](auto SEG, int stage, int ks) {
+#pragma unroll
+    for (int bt = 0; bt < BT; ++bt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        wf[stage][bt][j] = __builtin_bit_cast(
+            bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                        rw, w_lane + j * 1024, (int)((decltype(SEG)::value == 1 ? w_blkA[bt] : w_blkB[bt]) + (uint32_t)ks * w_plane), 0));
+  };
+  auto load_x = [&](auto SEG, int stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < XCH; ++i)
+      xr[stage][i] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                                                    rx, decltype(SEG)::value == 1 ? x_laneA : x_laneB, ks * (BK * 2) + i * 64 * K, 0));
+  };
+  auto store_x = [&](int stage, int buf) {
+#pragma unroll
+    for (int i = 0; i < XCH; ++i) *(bf16x8 *)(&xs[buf][x_lds + i * 32 * LDS_ROW]) = xr[stage][i];
+  };
+  using S0 = std::integral_constant<int, 0>; using S1 = std::integral_constant<int, 1>; using S2 = std::integral_constant<int, 2>;
+  using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>; using I3 = std::integral_constant<int, 3>;
+  using Y = std::true_type; using No = std::false_type;
+
+  load_x(S1{}, 0, 0);
+  load_w(S1{}, 0, 0);
+  load_x(S1{}, 1, 1);
+  load_w(S1{}, 1, 1);
+  load_w(S1{}, 2, 2);
+  store_x(0, 0);
+  __syncthreads();
+
+  const int a_off = (wm * AT * 32 + lrow) * LDS_ROW + half * 32;
+  // one k-step in ring slot u; LX / LW: segment whose x tile (k-step ksx) / W tiles (k-step ksw) are
+  // loaded meanwhile (S0: none); SX: whether the x tile loaded one step earlier goes to LDS
+  auto kstep = [&](auto U, auto LX, auto LW, auto SX, int ksx, int ksw) {
+    constexpr int u = decltype(U)::value;
+    constexpr bool lx = decltype(LX)::value != 0, lw = decltype(LW)::value != 0;
+    bf16x8 af[2][AT];
+    auto read_a = [&](int j) {
+#pragma unroll
+      for (int a = 0; a < AT; ++a) af[j & 1][a] = *(const bf16x8 *)(&xs[u & 1][a_off + a * 32 * LDS_ROW + j * 8]);
+    };
+    auto mma = [&](int j) {
+#pragma unroll
+      for (int a = 0; a < AT; ++a)
+#pragma unroll
+        for (int b = 0; b < BT; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[j & 1][a], wf[u][b][j], acc[a][b], 0, 0, 0);
+    };
+    read_a(0);
+    read_a(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (lx) load_x(LX, u & 1, ksx);
+    mma(0);
+    if constexpr (lx) {
+#pragma unroll
+      for (int i = 0; i < XCH; ++i) {
+        __builtin_amdgcn_sched_group_barrier(PL_SG_MFMA, (AT * BT) / XCH > 0 ? (AT * BT) / XCH : 1, 0);
+        __builtin_amdgcn_sched_group_barrier(PL_SG_VMEM_READ, 1, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    read_a(2);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (lw) load_w(LW, (u + 3) & 3, ksw);
+    mma(1);
+    if constexpr (lw) {
+#pragma unroll
+      for (int i = 0; i < BT * 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(PL_SG_MFMA, (AT * BT) / (BT * 4) > 0 ? (AT * BT) / (BT * 4) : 1, 0);
+        __builtin_amdgcn_sched_group_barrier(PL_SG_VMEM_READ, 1, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    read_a(3);
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (decltype(SX)::value) store_x((u + 1) & 1, (u + 1) & 1);
+    mma(2);
+    mma(3);
+    if constexpr (decltype(SX)::value) {
+#pragma unroll
+      for (int i = 0; i < XCH; ++i) {
+        __builtin_amdgcn_sched_group_barrier(PL_SG_MFMA, (2 * AT * BT) / XCH > 0 ? (2 * AT * BT) / XCH : 1, 0);
+        __builtin_amdgcn_sched_group_barrier(PL_SG_DS_WRITE, 1, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+  };
+
+  // tile A; its last three k-steps load the first operands of tile B
+  int ks = 0;
+  for (; ks < nksA - 4; ks += 4) {
+    kstep(I0{}, S1{}, S1{}, Y{}, ks + 2, ks + 3);
+    kstep(I1{}, S1{}, S1{}, Y{}, ks + 3, ks + 4);
+    kstep(I2{}, S1{}, S1{}, Y{}, ks + 4, ks + 5);
+    kstep(I3{}, S1{}, S1{}, Y{}, ks + 5, ks + 6);
+  }
+  kstep(I0{}, S1{}, S1{}, Y{}, ks + 2, ks + 3);
+  kstep(I1{}, S1{}, S2{}, Y{}, ks + 3, 0);
+  kstep(I2{}, S2{}, S2{}, Y{}, 0, 1);
+  kstep(I3{}, S2{}, S2{}, Y{}, 1, 2);
+
+  // epilogue of A (SwiGLU): accumulator register i of lane l is row (i/4)*8 + (l/32)*4 + i%4, column l%32
+#pragma unroll
+  for (int a = 0; a < AT; ++a) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = m0A + wm * AT * 32 + a * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+      if (m >= M) continue;
+      bf16_t *Y_ = mid + (int64_t)m * (N / 2);
+      if (n0A + lrow < n_main) {
+        const float gte = acc[a][0][i], up = acc[a][BT - 1][i];
+        const float sv = gte / (1.f + __expf(-gte));
+        Y_[(n0A >> 1) + lrow] = (__bf16)(sv * up);
+      }
+    }
+  }
+  zero_acc();
+
+  // K slice of tile B: its first two x tiles and three W tiles are already loaded or on the way
+  for (ks = 0; ks < nksB - 4; ks += 4) {
+    kstep(I0{}, S2{}, S2{}, Y{}, ks + 2, ks + 3);
+    kstep(I1{}, S2{}, S2{}, Y{}, ks + 3, ks + 4);
+    kstep(I2{}, S2{}, S2{}, Y{}, ks + 4, ks + 5);
+    kstep(I3{}, S2{}, S2{}, Y{}, ks + 5, ks + 6);
+  }
+  kstep(I0{}, S2{}, S2{}, Y{}, ks + 2, ks + 3);
+  kstep(I1{}, S2{}, S0{}, Y{}, ks + 3, 0);
+  kstep(I2{}, S0{}, S0{}, Y{}, 0, 0);
+  kstep(I3{}, S0{}, S0{}, No{}, 0, 0);
+
+  const int ldy = N - n_main;
+#pragma unroll
+  for (int a = 0; a < AT; ++a) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int m = m0B + wm * AT * 32 + a * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+      if (m >= M) continue;
+      float *Y_ = ws + ((int64_t)split * M + m) * ldy - n_main;
+#pragma unroll
+      for (int b = 0; b < BT; ++b) {
+        const int n = n0B + b * 32 + lrow;
+        if (n < N) Y_[n] = acc[a][b][i];
+      }
+    }
+  }
+}
+
 template <int WM, int WN, int AT, int BT, int MODE>
 __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
                                                    void *__restrict__ Yv, int M, int N, int K, int ksteps,
@@ -223,13 +421,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ X,
   gemm_tile<WM, WN, AT, BT, MODE>(xs, X, W, Yv, M, N, K, ksteps, n_base + ctile * BN, rtile * BM, blockIdx.y, n_end, ldy, y_col0);
 }
 
-// The SwiGLU product of a 129..256-row batch in ONE launch of one workgroup per compute unit.  Phase 1:
-// workgroup i computes main tile i (128 x 256, row tiles paired on an XCD as above) with the SwiGLU
-// epilogue.  Phase 2: the columns left over beyond the last full round of tiles, [n_main, N), are cut
-// into 128 x 256 tiles and those along K into `rem_splits` slices; workgroup i takes slice i % rem_splits
-// of tile i / rem_splits and writes its fp32 partial sums to ws, as a launch of the plain kernel with that
-// K split would (same slices, same k order); swiglu_reduce_kernel finishes them.  Every unit thus works
-// 56 + 12 k-steps at the 7B shape instead of 256 units 56 and then 160 units 56 more on quarter-size tiles.
+// The SwiGLU product of a 129..256-row batch in ONE launch of one workgroup per compute unit.  Workgroup i
+// computes main tile i (128 x 256, row tiles paired on an XCD as above) with the SwiGLU epilogue.  The
+// columns left over beyond the last full round of tiles, [n_main, N), are cut into 128 x 256 tiles and
+// those along K into `rem_splits` slices; workgroup i also takes slice i % rem_splits of tile
+// i / rem_splits and writes its fp32 partial sums to ws, as a launch of the plain kernel with that K
+// split would (same slices, same k order); swiglu_reduce_kernel finishes them.  A workgroup that has
+// both runs them back to back through gemm_tile2, the slice's first loads issued under the main tile's
+// last k-steps.  Every unit thus works 56 + 12 k-steps at the 7B shape instead of 256 units 56 and then
+// 160 units 56 more on quarter-size tiles.
 template <int WM, int WN, int AT, int BT>
 __global__ __launch_bounds__(256) void gemm_gu_fused_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
                                                             bf16_t *__restrict__ mid, float *__restrict__ ws, int M, int N,
@@ -237,17 +437,19 @@ __global__ __launch_bounds__(256) void gemm_gu_fused_kernel(const bf16_t *__rest
   constexpr int BM = WM * AT * 32, BN = WN * BT * 32;
   __shared__ __attribute__((aligned(16))) bf16_t xs[2][BM * LDS_ROW];
   const int nrow = (M + BM - 1) / BM;
-  {
-    const int rtile = (blockIdx.x >> 3) % nrow, ctile = (blockIdx.x / (8 * nrow)) * 8 + (blockIdx.x & 7);
-    if (ctile * BN < n_main)
-      gemm_tile<WM, WN, AT, BT, 1>(xs, X, W, mid, M, N, K, K / BK, ctile * BN, rtile * BM, 0, n_main, 0, 0);
-  }
+  const int rtileA = (blockIdx.x >> 3) % nrow, ctileA = (blockIdx.x / (8 * nrow)) * 8 + (blockIdx.x & 7);
+  const bool hasA = ctileA * BN < n_main;
   const int item = blockIdx.x / rem_splits, split = blockIdx.x % rem_splits;
   const int rem_ctiles = (N - n_main + BN - 1) / BN;
-  if (item >= rem_ctiles * nrow) return;
-  __syncthreads();   // the x tile of phase 1 is dead only when every wavefront has left its last k-step
-  const int ctile = item / nrow, rtile = item % nrow;
-  gemm_tile<WM, WN, AT, BT, 0>(xs, X, W, ws, M, N, K, rem_ksteps, n_main + ctile * BN, rtile * BM, split, N, N - n_main, n_main);
+  const bool hasB = item < rem_ctiles * nrow;
+  const int ctileB = item / nrow, rtileB = item % nrow;
+  if (hasA && hasB)   // uniform for the workgroup
+    gemm_tile2<WM, WN, AT, BT>(xs, X, W, mid, ws, M, N, K, ctileA * BN, rtileA * BM, n_main, n_main + ctileB * BN,
+                               rtileB * BM, split, rem_ksteps);
+  else if (hasA)
+    gemm_tile<WM, WN, AT, BT, 1>(xs, X, W, mid, M, N, K, K / BK, ctileA * BN, rtileA * BM, 0, n_main, 0, 0);
+  else if (hasB)
+    gemm_tile<WM, WN, AT, BT, 0>(xs, X, W, ws, M, N, K, rem_ksteps, n_main + ctileB * BN, rtileB * BM, split, N, N - n_main, n_main);
 }
 
 // SwiGLU over K-split partial sums: parts [splits][M][ld] holds columns [col0, col0 + ld) of the
