@@ -134,6 +134,10 @@ struct pl_engine {
   std::vector<hipEvent_t> ev_slot;   // per slot: end of its background prompt reading
   hipEvent_t ev_pre_last = nullptr;  // end of the last cache-only pass enqueued
   bool pre_pending = false;          // a cache-only pass may still be running
+  // per weight buffer: end of the last cache-only pass that was enqueued while that buffer was active
+  // (what a copy into the buffer, or a fill of it, has to wait for)
+  hipEvent_t ev_pre_buf[2] = {nullptr, nullptr};
+  bool pre_buf_pending[2] = {false, false};
   float *logits = nullptr;
   int32_t *tok_d = nullptr;
   float *lp_d = nullptr;
@@ -288,6 +292,7 @@ int alloc_device(pl_engine *e) {
   HIP_TRY(hipEventCreate(&e->ev_staged));
   HIP_TRY(hipEventCreate(&e->ev_copy0));
   HIP_TRY(hipEventCreateWithFlags(&e->ev_pre_last, hipEventDisableTiming));
+  for (auto &ev : e->ev_pre_buf) HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
   int rc;
   for (int b = 0; b < c.n_weight_buffers; ++b)
     if ((rc = dev_alloc(&e->wbuf[b], e->blob_elems * e->esz))) return rc;
@@ -622,6 +627,7 @@ int drain_passes(pl_engine *e) {
   if (e->pre_pending) {
     HIP_TRY(hipStreamSynchronize(e->wk[1].stream));
     e->pre_pending = false;
+    e->pre_buf_pending[0] = e->pre_buf_pending[1] = false;
   }
   harvest_passes(e);
   for (Seq &q : e->seqs) q.reading = false;
@@ -684,7 +690,11 @@ int run_kv_passes(pl_engine *e, const std::vector<int32_t> &slots, const std::ve
     }
     ++*passes;
   }
-  if (!e->dry && total) HIP_TRY(hipEventRecord(e->ev_pre_last, w.stream));
+  if (!e->dry && total) {
+    HIP_TRY(hipEventRecord(e->ev_pre_last, w.stream));
+    HIP_TRY(hipEventRecord(e->ev_pre_buf[e->active_buf], w.stream));
+    e->pre_buf_pending[e->active_buf] = true;
+  }
   return PL_OK;
 }
 
@@ -789,7 +799,7 @@ void pl_destroy(pl_engine *e) {
     for (hipEvent_t ev : e->ev_slot)
       if (ev) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : e->prof_ev) (void)hipEventDestroy(ev);
-    hipEvent_t evs[] = {e->ev_a, e->ev_b, e->ev_c, e->ev_staged, e->ev_copy0, e->ev_pre_last};
+    hipEvent_t evs[] = {e->ev_a, e->ev_b, e->ev_c, e->ev_staged, e->ev_copy0, e->ev_pre_last, e->ev_pre_buf[0], e->ev_pre_buf[1]};
     for (hipEvent_t ev : evs)
       if (ev) (void)hipEventDestroy(ev);
     if (e->s_dec) (void)hipStreamDestroy(e->s_dec);
@@ -900,9 +910,15 @@ int pl_swap_weights(pl_engine *e, const void *src, int64_t nbytes, uint32_t flag
   if (!e->dry) {
     HIP_TRY(hipSetDevice(e->cfg.device));
     if (e->cfg.n_weight_buffers == 2) {
-      // Steps are synchronous, so no decode kernel is reading the inactive buffer now; a prompt being
-      // read in the background may still be (it started before the last flip): the copy waits for it.
-      if (e->pre_pending) HIP_TRY(hipStreamWaitEvent(e->s_copy, e->ev_pre_last, 0));
+      // Steps are synchronous, so no decode kernel is reading the inactive buffer now; a prompt whose
+      // reading was enqueued before the last flip may still be: the copy waits for the last such pass
+      // (passes enqueued since the flip read the active buffer and do not hold the copy up).
+      const int tgt = e->active_buf ^ 1;
+      if (e->pre_buf_pending[tgt]) {
+        if (hipEventQuery(e->ev_pre_buf[tgt]) == hipSuccess) e->pre_buf_pending[tgt] = false;
+        else HIP_TRY(hipStreamWaitEvent(e->s_copy, e->ev_pre_buf[tgt], 0));
+        (void)hipGetLastError();
+      }
       HIP_TRY(hipEventRecord(e->ev_copy0, e->s_copy));
       HIP_TRY(hipMemcpyAsync(e->wbuf[e->active_buf ^ 1], src, (size_t)nbytes, hipMemcpyDefault, e->s_copy));
       int rc = tie_lm_head(e, e->active_buf ^ 1, e->s_copy);
@@ -1072,7 +1088,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       // still does shows up in the logits.  The next staging copy overwrites the buffer; it cannot start
       // before this step has ended (steps are synchronous).  A prompt being read in the background was
       // enqueued under the old weights and is entitled to them: the fill waits for the last such pass.
-      if (e->pre_pending) HIP_TRY(hipStreamWaitEvent(e->s_dec, e->ev_pre_last, 0));
+      if (e->pre_buf_pending[e->active_buf ^ 1]) HIP_TRY(hipStreamWaitEvent(e->s_dec, e->ev_pre_buf[e->active_buf ^ 1], 0));
       if (pl::launch_fill_u32((uint32_t *)e->wbuf[e->active_buf ^ 1], e->f32 ? 0x7FC00000u : 0x7FC07FC0u,
                               e->blob_elems * e->esz / 4, e->s_dec))
         return fail(PL_E_HIP, "fill launch failed");
