@@ -800,7 +800,7 @@ def main():
     res["hbm_read_stream_ceiling_nontemporal_GBs"] = stream_ceiling(torch, pl, nontemporal=True)
     if d["attn_launches"]:
         # The kernel's figure is taken from the launches that had the GPU to themselves; launches of steps that
-        # shared it with a background prompt-reading pass are reported beside it.
+        # shared it with a background prompt-reading pass or with the staging copy of an update are reported beside it.
         alone = d["attn_launches"] - d["attn_shared_launches"]
         if alone:
             per_launch_bytes = (d["attn_kv_bytes"] - d["attn_shared_kv_bytes"]) / alone
@@ -812,8 +812,8 @@ def main():
                            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                            "launches": int(alone or d["attn_launches"]),
                            "timed_on": f"one timed step in {prof_every}" if prof_every > 1 else "every timed step",
-                           "launches_beside_a_background_pass": int(d["attn_shared_launches"]),
-                           "achieved_beside_a_background_pass": (d["attn_shared_kv_bytes"] / d["attn_shared_ms"] / 1e6
+                           "launches_beside_a_background_pass_or_copy": int(d["attn_shared_launches"]),
+                           "achieved_beside_a_background_pass_or_copy": (d["attn_shared_kv_bytes"] / d["attn_shared_ms"] / 1e6
                                                                  if d["attn_shared_launches"] else None),
                            # HBM bytes per launch from the rocprofv3 counter runs of this same command
                            # (FETCH_SIZE and WRITE_SIZE, scaled on plain copies), as recorded in profiles/

@@ -112,7 +112,8 @@ typedef struct {
                                           * that merges the chunks of long rows is timed under other_ms), GEMM launches */
   double attn_kv_bytes;                  /* K/V bytes those attention launches had to read */
   /* the part of the three attention figures above that was measured in steps during which a background
-   * cache-only pass (pl_prefill_async) was in flight, i.e. while the kernel shared the GPU */
+   * cache-only pass (pl_prefill_async) or the staging copy of an update was in flight, i.e. while the
+   * kernel shared the GPU or its memory */
   double attn_shared_ms, attn_shared_kv_bytes;
   uint64_t attn_shared_launches;
   /* host time inside pl_decode_step, summed over steps: from entry until the step's work is enqueued,

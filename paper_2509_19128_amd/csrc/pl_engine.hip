@@ -1043,7 +1043,7 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
     }
   }
   if (!e->dry && !n_reading && e->pre_pending && hipEventQuery(e->ev_pre_last) == hipSuccess) e->pre_pending = false;
-  const bool shared_gpu = e->pre_pending;   // a cache-only pass may run beside this step's kernels
+  bool shared_gpu = e->pre_pending;   // a cache-only pass may run beside this step's kernels
   int n = 0;
   int64_t new_pages = 0;
   for (int s = 0; s < c.max_batch; ++s) {
@@ -1111,6 +1111,8 @@ int pl_decode_step(pl_engine *e, const int32_t *forced, pl_step_out *out) {
       if (rc) return rc;
     }
   }
+
+  if (e->staged && !e->dry) shared_gpu = true;   // the staging copy of an update is still writing to HBM beside this step
 
   // 3. pages and per-step metadata
   pl_engine::Work &w = e->wk[0];
