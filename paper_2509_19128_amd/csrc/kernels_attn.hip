@@ -67,11 +67,15 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
 
   const int nblk = (t1 - t0 + 31) >> 5;
   const int64_t page_elems = (int64_t)2 * p.page_tokens * HD;   // K block + V block of one kv head
-  auto run_base = [&](int blk) -> const bf16_t * {
-    int t = t0 + blk * 32;
+  // page id of a run, and the address of its K fragments given that id: the id of the run a stage will
+  // hold next is fetched one refill ahead, so that no K/V load waits for a page-table load
+  auto page_of = [&](int blk) -> int {
+    const int t = t0 + blk * 32;
     const int rel = t / p.page_tokens - page_first;
-    int page = rel == 0 ? r1.x : rel == 1 ? r1.y : rel == 2 ? r1.z : rel == 3 ? r1.w : pt[t / p.page_tokens];
-    int r = (t % p.page_tokens) >> 5;
+    return rel == 0 ? r1.x : rel == 1 ? r1.y : rel == 2 ? r1.z : rel == 3 ? r1.w : pt[t / p.page_tokens];
+  };
+  auto run_base = [&](int blk, int page) -> const bf16_t * {
+    const int r = ((t0 + blk * 32) % p.page_tokens) >> 5;
     return p.kv + ((int64_t)page * p.Hkv + g) * page_elems + (int64_t)r * 32 * HD + l * 8;
   };
 
@@ -93,10 +97,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
 #pragma unroll
     for (int i = 0; i < NV; ++i) vf[st][i] = __builtin_nontemporal_load((const bf16x8 *)(vb + i * 512));
   };
+  int page_next[NS];   // page of the run stage st takes after the one it holds
 #pragma unroll
   for (int st = 0; st < NS; ++st) {
     const int b0 = wave + 4 * st;
-    if (b0 < nblk) { const bf16_t *kb = run_base(b0); load_k(st, kb); load_v(st, kb); }
+    if (b0 < nblk) { const bf16_t *kb = run_base(b0, page_of(b0)); load_k(st, kb); load_v(st, kb); }
+    page_next[st] = b0 + 4 * NS < nblk ? page_of(b0 + 4 * NS) : 0;
   }
   for (int base = wave; base < nblk; base += 4 * NS) {
 #pragma unroll
@@ -114,7 +120,11 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
         }
         const int nxt = blk + 4 * NS;
         const bf16_t *nb = nullptr;
-        if (nxt < nblk) { nb = run_base(nxt); load_k(st, nb); }
+        if (nxt < nblk) {
+          nb = run_base(nxt, page_next[st]);
+          load_k(st, nb);
+          page_next[st] = nxt + 4 * NS < nblk ? page_of(nxt + 4 * NS) : 0;
+        }
         const int tbase = t0 + blk * 32 + qg * 8;
         float s[8];
         float mb = -INFINITY;
