@@ -31,14 +31,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
   // consecutive workgroup ids, which the hardware deals round-robin to the 8 XCDs, load all XCDs
   // evenly whatever the mix of context lengths.  An item is one 32-byte record (sequence, chunk,
   // context length, slot, and the first four page ids of the chunk), so that the first K/V loads of
-  // a workgroup are two dependent scalar loads away (list length, record) instead of five: with the
-  // memory system saturated each such load takes about a microsecond during which the workgroup has
-  // nothing in flight.
+  // a workgroup are one dependent scalar load away (its record; records beyond the list's end say so
+  // themselves) instead of five: with the memory system saturated each such load takes about a
+  // microsecond during which the workgroup has nothing in flight.
   const int item = blockIdx.x / p.Hkv, g = blockIdx.x % p.Hkv;
-  if (item >= p.work[0]) return;
   const int4 *rec = (const int4 *)(p.work + 8 + 8 * (int64_t)item);
   const int4 r0 = rec[0], r1 = rec[1];
   const int b = r0.x, c = r0.y, ctx = r0.z, slot = r0.w;
+  if (ctx <= 0) return;   // beyond the end of the list (the list kernel clears the records up to the buffer's end)
   const int t0 = c * p.chunk;
   const int t1 = min(ctx, t0 + p.chunk);
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
@@ -263,6 +263,11 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
   const int mi = block_scan_1024(n > 1, wsum, &n_multi) - (n > 1);
   if (n > 1) multi[mi] = b;
   if (b == 0) { work[0] = total_full + n_last; work[1] = n_multi; }
+  // records beyond the list's end, up to the end of the record area (the multi list starts there), say
+  // "no item": a workgroup of the decode kernel learns that from its own record, without a second
+  // dependent load of the list's length
+  const int cap = (int)((multi - (work + 8)) / 8);
+  for (int i = total_full + n_last + b; i < cap; i += 1024) ((int4 *)(work + 8 + 8 * (int64_t)i))[0] = make_int4(0, 0, 0, 0);
 }
 
 // Merge of the chunks of multi-chunk sequences, in chunk order.  One workgroup of HD threads per
