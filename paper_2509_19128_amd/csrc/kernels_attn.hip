@@ -215,7 +215,8 @@ __device__ inline int block_scan_1024(int v, int *wsum, int *total) {
   return v + before;
 }
 
-// work[0] = number of items, work[1] = number of sequences longer than one chunk (listed in `multi`);
+// work[0] = number of items, work[1] = number of sequences longer than one chunk (listed in `multi` as
+// row | chunks << 12, the rest of the list -1);
 // the items are 8-int records from work[8] on: {sequence, chunk, context length, slot, ids of the
 // chunk's first four pages}.  All full chunks come first, then each
 // sequence's last (partial or full) chunk, longest first, so that the workgroups still running when
@@ -261,7 +262,8 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
   // rows that span several chunks, in row order: what the merge kernel walks
   int n_multi;
   const int mi = block_scan_1024(n > 1, wsum, &n_multi) - (n > 1);
-  if (n > 1) multi[mi] = b;
+  if (n > 1) multi[mi] = b | (n << 12);   // row and its number of chunks in one word (n_seq <= 1024)
+  for (int i = n_multi + b; i < n_seq; i += 1024) multi[i] = -1;   // beyond the list's end
   if (b == 0) { work[0] = total_full + n_last; work[1] = n_multi; }
   // records beyond the list's end, up to the end of the record area (the multi list starts there), say
   // "no item": a workgroup of the decode kernel learns that from its own record, without a second
@@ -279,11 +281,12 @@ __global__ __launch_bounds__(1024) void attn_worklist_kernel(const int32_t *ctx_
 template <int HD>
 __global__ __launch_bounds__(HD < 64 ? 64 : HD) void attn_combine_kernel(AttnParams p) {
   constexpr int NT = HD < 64 ? 64 : HD;   // threads: whole wavefronts; thread d < HD owns output element d
-  if ((int)blockIdx.y >= p.work[1]) return;
-  const int b = p.multi[blockIdx.y], hq = blockIdx.x;
+  // one list entry = row | number of chunks << 12, negative beyond the list's end: the chunk statistics
+  // are one dependent load away
+  const int entry = p.multi[blockIdx.y];
+  if (entry < 0) return;
+  const int b = entry & 0xFFF, nchunk = entry >> 12, hq = blockIdx.x;
   const int G = p.Hq / p.Hkv, g = hq / G, h = hq % G;
-  const int ctx = p.ctx_len[b];
-  const int nchunk = (ctx + p.chunk - 1) / p.chunk;
   const int64_t base = ((int64_t)b * p.Hkv + g) * p.max_chunks;
   const float *ml = p.part_ml + (base * G + h) * 2;                   // chunk c at ml[c * G * 2]
   const float *po = p.part_o + (base * G + h) * HD + (threadIdx.x < HD ? threadIdx.x : 0);   // chunk c at po[c * G * HD]
